@@ -1,0 +1,226 @@
+"""numpy front end of the CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+Loads ``libequarx_oracle.so`` (built from ``equarx_oracle.c`` with gcc) and
+exposes its functions on numpy arrays.  bf16 tensors travel as ``uint16``
+arrays holding the raw bit patterns.  Nothing here touches the GPU or the HIP
+library; only tests, the smoke check and the benchmark's cpu_baseline leg may
+import this module.
+
+The arithmetic lives in the C file; this module only marshals arguments.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "equarx_oracle.c")
+_LIB = os.path.join(_HERE, "libequarx_oracle.so")
+
+# Every rounding is written out in the source; the flags keep the compiler from
+# changing any of them (no contraction into FMAs, no value-changing shortcuts).
+_CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC", "-std=c11"]
+
+
+def build(force: bool = False, src: str = _SRC, lib: str = _LIB, extra_flags=()) -> str:
+    """Compile the C oracle with gcc.  Returns the path of the shared library."""
+    if not force and os.path.exists(lib) and os.path.getmtime(lib) >= os.path.getmtime(src):
+        return lib
+    cmd = ["gcc", *_CFLAGS, *extra_flags, src, "-o", lib, "-lm"]
+    subprocess.run(cmd, check=True)
+    return lib
+
+
+_c_i8p = ctypes.POINTER(ctypes.c_int8)
+_c_u16p = ctypes.POINTER(ctypes.c_uint16)
+_c_f32p = ctypes.POINTER(ctypes.c_float)
+_c_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+def _declare(lib: ctypes.CDLL) -> ctypes.CDLL:
+    i64, i32 = ctypes.c_int64, ctypes.c_int32
+    pp = ctypes.POINTER(_c_u16p)
+    lib.equarx_oracle_set_threads.argtypes = [ctypes.c_int]
+    lib.equarx_oracle_set_threads.restype = None
+    lib.equarx_oracle_get_threads.argtypes = []
+    lib.equarx_oracle_get_threads.restype = ctypes.c_int
+    lib.equarx_oracle_has_openmp.argtypes = []
+    lib.equarx_oracle_has_openmp.restype = ctypes.c_int
+    lib.equarx_oracle_bf16_to_f32.argtypes = [_c_u16p, i64, _c_f32p]
+    lib.equarx_oracle_f32_to_bf16.argtypes = [_c_f32p, i64, _c_u16p]
+    lib.equarx_oracle_quantize_f32.argtypes = [_c_f32p, i64, i32, _c_i8p, _c_f32p]
+    lib.equarx_oracle_quantize_bf16.argtypes = [_c_u16p, i64, i32, _c_i8p, _c_f32p]
+    lib.equarx_oracle_dequantize_f32.argtypes = [_c_i8p, _c_f32p, i64, i32, _c_f32p]
+    lib.equarx_oracle_dequantize_bf16.argtypes = [_c_i8p, _c_f32p, i64, i32, _c_u16p]
+    lib.equarx_oracle_hop.argtypes = [_c_i8p, _c_f32p, _c_u16p, i64, i32, _c_i8p, _c_f32p]
+    lib.equarx_oracle_reduce_chain.argtypes = [pp, i32, i64, i32, _c_u16p, _c_i8p, _c_f32p]
+    lib.equarx_oracle_exact_sum_f64.argtypes = [pp, i32, i64, _c_f64p]
+    lib.equarx_oracle_sum_f32.argtypes = [pp, i32, i64, _c_f32p]
+    for name in ("bf16_to_f32", "f32_to_bf16", "quantize_f32", "quantize_bf16", "dequantize_f32",
+                 "dequantize_bf16", "hop", "reduce_chain", "exact_sum_f64", "sum_f32"):
+        getattr(lib, "equarx_oracle_" + name).restype = None
+    return lib
+
+
+def load(lib_path: str | None = None) -> ctypes.CDLL:
+    """Load (building first if needed) the oracle library."""
+    path = lib_path or build()
+    return _declare(ctypes.CDLL(path))
+
+
+_lib = None
+
+
+def _L() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = load()
+    return _lib
+
+
+def _arr(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a.reshape(-1)
+
+
+def _ptr(a: np.ndarray, ctype):
+    return a.ctypes.data_as(ctype)
+
+
+def _check_block(B: int) -> int:
+    B = int(B)
+    if B < 1:
+        raise ValueError("block size must be >= 1")
+    return B
+
+
+def num_blocks(n: int, B: int) -> int:
+    return (int(n) + int(B) - 1) // int(B)
+
+
+def set_threads(threads: int) -> None:
+    _L().equarx_oracle_set_threads(int(threads))
+
+
+def get_threads() -> int:
+    return int(_L().equarx_oracle_get_threads())
+
+
+def bf16_to_f32(x_u16) -> np.ndarray:
+    x = _arr(x_u16, np.uint16)
+    out = np.empty(x.size, np.float32)
+    _L().equarx_oracle_bf16_to_f32(_ptr(x, _c_u16p), x.size, _ptr(out, _c_f32p))
+    return out
+
+
+def f32_to_bf16(v) -> np.ndarray:
+    v = _arr(v, np.float32)
+    out = np.empty(v.size, np.uint16)
+    _L().equarx_oracle_f32_to_bf16(_ptr(v, _c_f32p), v.size, _ptr(out, _c_u16p))
+    return out
+
+
+def quantize_f32(v, B: int, lib=None):
+    """Q_B of an fp32 tensor -> (codes int8 [n], scales fp32 [ceil(n/B)])."""
+    B = _check_block(B)
+    v = _arr(v, np.float32)
+    codes = np.empty(v.size, np.int8)
+    scales = np.empty(num_blocks(v.size, B), np.float32)
+    (lib or _L()).equarx_oracle_quantize_f32(_ptr(v, _c_f32p), v.size, B, _ptr(codes, _c_i8p), _ptr(scales, _c_f32p))
+    return codes, scales
+
+
+def quantize_bf16(x_u16, B: int, lib=None):
+    """Q_B of a bf16 tensor (uint16 bit patterns) -> (codes, scales)."""
+    B = _check_block(B)
+    x = _arr(x_u16, np.uint16)
+    codes = np.empty(x.size, np.int8)
+    scales = np.empty(num_blocks(x.size, B), np.float32)
+    (lib or _L()).equarx_oracle_quantize_bf16(_ptr(x, _c_u16p), x.size, B, _ptr(codes, _c_i8p), _ptr(scales, _c_f32p))
+    return codes, scales
+
+
+def dequantize_f32(codes, scales, B: int, lib=None) -> np.ndarray:
+    B = _check_block(B)
+    c = _arr(codes, np.int8)
+    s = _arr(scales, np.float32)
+    assert s.size == num_blocks(c.size, B)
+    out = np.empty(c.size, np.float32)
+    (lib or _L()).equarx_oracle_dequantize_f32(_ptr(c, _c_i8p), _ptr(s, _c_f32p), c.size, B, _ptr(out, _c_f32p))
+    return out
+
+
+def dequantize_bf16(codes, scales, B: int, lib=None) -> np.ndarray:
+    B = _check_block(B)
+    c = _arr(codes, np.int8)
+    s = _arr(scales, np.float32)
+    assert s.size == num_blocks(c.size, B)
+    out = np.empty(c.size, np.uint16)
+    (lib or _L()).equarx_oracle_dequantize_bf16(_ptr(c, _c_i8p), _ptr(s, _c_f32p), c.size, B, _ptr(out, _c_u16p))
+    return out
+
+
+def hop(codes_in, scales_in, local_u16, B: int, lib=None):
+    """One receive step: dequantize, add the local bf16 shard in fp32, requantize."""
+    B = _check_block(B)
+    c = _arr(codes_in, np.int8)
+    s = _arr(scales_in, np.float32)
+    x = _arr(local_u16, np.uint16)
+    assert x.size == c.size and s.size == num_blocks(c.size, B)
+    codes = np.empty(c.size, np.int8)
+    scales = np.empty(s.size, np.float32)
+    (lib or _L()).equarx_oracle_hop(_ptr(c, _c_i8p), _ptr(s, _c_f32p), _ptr(x, _c_u16p), c.size, B,
+                                    _ptr(codes, _c_i8p), _ptr(scales, _c_f32p))
+    return codes, scales
+
+
+def _pointer_table(partials):
+    arrs = [_arr(p, np.uint16) for p in partials]
+    if not arrs:
+        raise ValueError("need at least one partial")
+    n = arrs[0].size
+    if any(a.size != n for a in arrs):
+        raise ValueError("partials differ in length")
+    table = (_c_u16p * len(arrs))(*[_ptr(a, _c_u16p) for a in arrs])
+    return arrs, table, n
+
+
+def reduce_chain(partials, B: int, keep_wire: bool = False, lib=None):
+    """The full-loop adder chain with reduce-scatter and all-gather both quantized.
+
+    partials: sequence of P bf16 tensors (uint16), in chain order.
+    Returns out (uint16 [n]); with keep_wire also (wire_codes [P, n], wire_scales [P, nb]).
+    """
+    B = _check_block(B)
+    arrs, table, n = _pointer_table(partials)
+    P = len(arrs)
+    nb = num_blocks(n, B)
+    out = np.empty(n, np.uint16)
+    if keep_wire:
+        wc = np.empty((P, n), np.int8)
+        ws = np.empty((P, nb), np.float32)
+        wcp, wsp = _ptr(wc, _c_i8p), _ptr(ws, _c_f32p)
+    else:
+        wc = ws = None
+        wcp, wsp = None, None
+    (lib or _L()).equarx_oracle_reduce_chain(table, P, n, B, _ptr(out, _c_u16p), wcp, wsp)
+    if keep_wire:
+        return out, wc, ws
+    return out
+
+
+def exact_sum_f64(partials, lib=None) -> np.ndarray:
+    arrs, table, n = _pointer_table(partials)
+    ref = np.empty(n, np.float64)
+    (lib or _L()).equarx_oracle_exact_sum_f64(table, len(arrs), n, _ptr(ref, _c_f64p))
+    return ref
+
+
+def sum_f32(partials, lib=None) -> np.ndarray:
+    arrs, table, n = _pointer_table(partials)
+    ref = np.empty(n, np.float32)
+    (lib or _L()).equarx_oracle_sum_f32(table, len(arrs), n, _ptr(ref, _c_f32p))
+    return ref

@@ -1,0 +1,81 @@
+"""Plants one mistake at a time in a COPY of the oracle's source (CPU only) and checks the pins notice.
+
+This is what makes the pins trustworthy: a dropped abs, a wrong divisor, the
+wrong rounding mode, an unfused multiply-add, a wrong scale or partial index,
+a transposed operand -- each must fail at least one pin.  The real oracle is
+untouched; mutants are compiled into a temporary directory.
+"""
+import os
+
+import pytest
+
+import oracle_pins
+from oracle import equarx_oracle as o
+
+MUTANTS = {
+    # name: (text in the oracle's source, replacement)
+    "no_abs": ("float m = fabsf(v[j]);", "float m = v[j];"),
+    "divisor_128": ("scale = a / 127.0f;", "scale = a / 128.0f;"),
+    "inv_from_scale": ("inv = 127.0f / a;", "inv = 1.0f / scale;"),
+    "inv_128": ("inv = 127.0f / a;", "inv = 128.0f / a;"),
+    "round_half_away": ("r = nearbyintf(r);", "r = roundf(r);"),
+    "truncate": ("r = nearbyintf(r);", "r = truncf(r);"),
+    "divide_instead_of_multiply": ("float r = v[j] * inv;", "float r = (scale > 0.0f) ? v[j] / scale : 0.0f;"),
+    "no_tiny_threshold": ("if (a < 127.0f * FLT_MIN) {", "if (a == 0.0f) {"),
+    "unfused_add": ("t[j] = fmaf((float)codes_in[at + j], scales_in[b], widen_bf16(local[at + j]));",
+                    "t[j] = (float)codes_in[at + j] * scales_in[b] + widen_bf16(local[at + j]);"),
+    "hop_subtracts": ("t[j] = fmaf((float)codes_in[at + j], scales_in[b], widen_bf16(local[at + j]));",
+                      "t[j] = fmaf((float)codes_in[at + j], scales_in[b], -widen_bf16(local[at + j]));"),
+    "hop_wrong_scale": ("t[j] = fmaf((float)codes_in[at + j], scales_in[b], widen_bf16(local[at + j]));",
+                        "t[j] = fmaf((float)codes_in[at + j], scales_in[0], widen_bf16(local[at + j]));"),
+    "hop_quantizes_local": ("t[j] = fmaf((float)codes_in[at + j], scales_in[b], widen_bf16(local[at + j]));",
+                            "t[j] = fmaf((float)codes_in[at + j], scales_in[b], nearbyintf(widen_bf16(local[at + j]) * 64.0f) / 64.0f);"),
+    "dequant_wrong_block": ("float d = (float)codes[j] * scales[j / B];", "float d = (float)codes[j] * scales[0];"),
+    "dequant_f32_wrong_block": ("out[j] = (float)codes[j] * scales[j / B];", "out[j] = (float)codes[j] * scales[(j + 1) / B];"),
+    "bf16_round_half_up": ("if (drop > 0x8000u || (drop == 0x8000u && (keep & 1u))) {", "if (drop >= 0x8000u) {"),
+    "bf16_truncate": ("if (drop > 0x8000u || (drop == 0x8000u && (keep & 1u))) {", "if (0) {"),
+    "chain_reuses_first_partial": ("equarx_oracle_hop(c_prev, s_prev, partials[i], n, B, c_next, s_next);",
+                                   "equarx_oracle_hop(c_prev, s_prev, partials[0], n, B, c_next, s_next);"),
+    "chain_skips_last": ("for (int32_t i = 1; i < P; ++i) {\n        equarx_oracle_hop(",
+                         "for (int32_t i = 1; i < P - 1; ++i) {\n        equarx_oracle_hop("),
+    "chain_no_swap": ("int8_t *tc = c_prev; c_prev = c_next; c_next = tc;", "int8_t *tc = c_prev; (void)tc;"),
+    "chain_out_not_requantized": ("equarx_oracle_dequantize_bf16(c_prev, s_prev, n, B, out);",
+                                  "equarx_oracle_dequantize_bf16(c_next, s_next, n, B, out);"),
+    "f32_sum_in_f64": ("for (int32_t i = 1; i < P; ++i) acc = acc + widen_bf16(partials[i][j]);",
+                       "double a2 = acc; for (int32_t i = 1; i < P; ++i) a2 += widen_bf16(partials[i][j]); acc = (float)a2;"),
+    "exact_sum_drops_last": ("for (int32_t i = 0; i < P; ++i) acc += (double)widen_bf16(partials[i][j]);",
+                             "for (int32_t i = 0; i + 1 < P; ++i) acc += (double)widen_bf16(partials[i][j]);"),
+}
+
+
+def _failing_pins(lib, first_only=False):
+    failed = []
+    for pin in oracle_pins.ALL_PINS:
+        try:
+            pin(lib)
+        except AssertionError:
+            failed.append(pin.__name__)
+            if first_only:
+                break
+    return failed
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_pins_catch_mutant(oracle, tmp_path, name):
+    old, new = MUTANTS[name]
+    with open(os.path.join(os.path.dirname(o.__file__), "equarx_oracle.c")) as f:
+        src = f.read()
+    assert src.count(old) == 1, f"mutation site for {name} not found exactly once"
+    mutated = tmp_path / "mutant.c"
+    mutated.write_text(src.replace(old, new))
+    lib_path = o.build(force=True, src=str(mutated), lib=str(tmp_path / "libmutant.so"))
+    lib = o.load(lib_path)
+    failed = _failing_pins(lib, first_only=True)
+    assert failed, f"no pin noticed the planted mistake {name!r}"
+
+
+def test_unmutated_copy_passes(oracle, tmp_path):
+    """The harness itself: an unchanged copy of the source passes every pin."""
+    src = os.path.join(os.path.dirname(o.__file__), "equarx_oracle.c")
+    lib = o.load(o.build(force=True, src=src, lib=str(tmp_path / "libcopy.so")))
+    assert _failing_pins(lib) == []
