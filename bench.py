@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized P-way reduction on one MI355X.
+
+A step is one pass of the whole hot path -- quantize, P-1 fused dequantize-add-requantize hops, final
+dequantize (equarx_reduce_quantized) -- over one batch of synthetic partial sums already resident in HBM.
+Prints ONE JSON line: effective input GB/s (bf16 bytes reduced per second), the roofline of the dominant
+kernel (the hop) from per-launch HIP event timings, and the CPU oracle timed on the host as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published peak
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hop_kernel_c3_traffic.txt")
+
+
+def hop_bytes(n: int, block: int) -> float:
+    """Algorithmic bytes of one hop launch: bf16 shard in, codes+scales in, codes+scales out."""
+    return n * (2.0 + 2.0 * (1.0 + 4.0 / block))
+
+
+def chain_bytes(P: int, n: int, block: int) -> float:
+    """Algorithmic bytes of the hop-by-hop schedule: every wire buffer written once and read once."""
+    return n * (2.0 * P + 2.0 * P * (1.0 + 4.0 / block) + 2.0)
+
+
+def read_traffic():
+    """HBM bytes per hop launch from the committed rocprofv3 counter summary, or None."""
+    try:
+        vals = {}
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                if line.startswith("hbm_bytes_per_launch"):
+                    vals["t"] = float(line.split()[1])
+        return vals.get("t")
+    except OSError:
+        return None
+
+
+def cpu_baseline(w, host_u16, budget_s: float):
+    """The oracle as it stands, timed on this machine's host cores on the same workload."""
+    from oracle import equarx_oracle as orc
+    orc.build()
+    threads = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16") or 16)))
+    orc.set_threads(threads)
+    times = []
+    t_end = time.perf_counter() + budget_s
+    while len(times) < 10 and (not times or time.perf_counter() + times[-1] < t_end):
+        t0 = time.perf_counter()
+        orc.reduce_chain(host_u16, w.block)
+        times.append(time.perf_counter() - t0)
+    best = statistics.median(times)
+    return {
+        "value": round(2.0 * w.P * w.n / best / 1e9, 4),
+        "unit": "GB/s effective input",
+        "cores": orc.get_threads(),
+        "kind": "oracle",
+        "sample": f"whole workload ({w.P} x {w.n} bf16), median of {len(times)} full chains, {best * 1e3:.0f} ms each",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c3_gemma3_27b")
+    ap.add_argument("--block", type=int, default=0, help="override the workload's block size")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing; 0 skips it")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all P partials live in one MI355X's HBM); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2506_17615_amd import binding as eq
+    from paper_2506_17615_amd import workloads as wl
+
+    eq.load()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    w = wl.WORKLOADS[args.workload]
+    if args.block:
+        w = w.with_block(args.block)
+    K, W = args.steps, args.warmup
+    P, n, B = w.P, w.n, w.block
+
+    host = wl.make_partials(w)
+    # two resident input sets, used in turn, so that no step finds its inputs in the 256 MB Infinity Cache
+    sets = [[p.reshape(-1).cuda() for p in host]]
+    sets.append([p.clone() for p in sets[0]])
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    work = eq.alloc_workspace(P, n, B)
+    nb = eq.num_blocks(n, B)
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for k in range(W):
+            eq.equarx_reduce_quantized(sets[k % 2], B, out, work)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(K):
+            eq.equarx_reduce_quantized(sets[k % 2], B, out, work)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / K
+
+        # error of the result against the exact sum (fp64), computed with torch on the GPU
+        eq.equarx_reduce_quantized(sets[0], B, out, work)
+        ref = torch.zeros(n, dtype=torch.float64, device="cuda")
+        for p in sets[0]:
+            ref += p.double()
+        diff = out.double() - ref
+        rel_l2 = float(diff.norm() / ref.norm())
+        mse = float((diff * diff).mean())
+        max_abs = float(diff.abs().max())
+        del ref, diff
+
+        # the same K steps, taken apart through the per-stage entry points, each hop launch carrying its own
+        # pair of HIP events: the dominant kernel's duration, launch by launch
+        codes = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(2)]
+        scales = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(2)]
+        pairs = []
+        for _ in range(K * max(P - 1, 1)):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            b.record(stream)          # creates the underlying hipEvent_t handles
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        it = iter(pairs)
+        used = []
+        for k in range(K):
+            parts = sets[k % 2]
+            if P == 1:
+                a, b = next(it)
+                eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
+                used.append((a, b))
+            eq.equarx_quantize(parts[0], B, codes[0], scales[0])
+            for i in range(1, P):
+                a, b = next(it)
+                eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
+                used.append((a, b))
+                eq.equarx_reduce_stage(codes[(i - 1) & 1], scales[(i - 1) & 1], parts[i], B, codes[i & 1], scales[i & 1])
+            eq.equarx_dequantize(codes[(P - 1) & 1], scales[(P - 1) & 1], B, out)
+        torch.cuda.synchronize()
+        durs_ms = [a.elapsed_time(b) for a, b in used]
+        kernel_ms = statistics.fmean(durs_ms)
+
+        # calibration: what a plain 16-byte copy reaches on this device over the same footprint
+        src = torch.empty(2 * P * n // 2, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            eq.equarx_calib_copy(src, dst)
+        cp = []
+        for _ in range(10):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            b.record(stream)
+            torch.cuda.synchronize()
+            eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
+            eq.equarx_calib_copy(src, dst)
+            torch.cuda.synchronize()
+            cp.append(a.elapsed_time(b))
+        copy_gbps = 2.0 * src.numel() / (statistics.median(cp) * 1e-3) / 1e9
+
+    dominant = "hop (dequantize + fp32 add + requantize)" if P > 1 else "quantize"
+    per_launch = hop_bytes(n, B) if P > 1 else n * (2.0 + 1.0 + 4.0 / B)
+    achieved = per_launch / (kernel_ms * 1e-3) / 1e9
+    value = 2.0 * P * n / (ms_per_step * 1e-3) / 1e9
+    chain_frac = chain_bytes(P, n, B) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS
+
+    result = {
+        "metric": "effective input GB/s (bf16 bytes reduced/sec)",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "P": P, "rows": w.rows, "hidden": w.hidden, "n": n, "block": B,
+                   "distribution": w.dist, "schedule": "hop-by-hop, P+1 launches, wire written once and read once"},
+        "chain": {"algorithmic_bytes": chain_bytes(P, n, B), "frac_of_hbm_peak": round(chain_frac, 4)},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(),
+                     "bytes_per_launch": per_launch, "avg_launch_us": round(kernel_ms * 1e3, 3),
+                     "launches_timed": len(durs_ms), "copy_kernel_GBps": round(copy_gbps, 1)},
+        "error_vs_exact_sum": {"rel_l2": rel_l2, "mse": mse, "max_abs": max_abs},
+    }
+    if args.cpu_seconds > 0:
+        result["cpu_baseline"] = cpu_baseline(w, [wl.as_u16(p) for p in host], args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,148 @@
+/*
+ * libequarx -- block-wise int8 quantized P-way reduction on one MI355X (gfx950).
+ *
+ * The compute path of EQuARX (arXiv 2506.17615): what each device does to the
+ * data of a quantized AllReduce, with the inter-chip transfers replaced by
+ * reads of buffers that live in the same GPU's HBM.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers (HBM of the current device) unless
+ *     a parameter says HOST.  The caller owns every buffer; the library never
+ *     allocates, frees or keeps a pointer after the call returns.
+ *   - bf16 tensors are raw 16-bit patterns (upper half of an IEEE binary32).
+ *   - A tensor of n elements is flat and contiguous.  Block b covers elements
+ *     [b*block, min(n, (b+1)*block)); nb = ceil(n / block) blocks.  For a
+ *     [rows, hidden] activation with hidden % block == 0, blocks run along
+ *     hidden and never straddle rows.
+ *   - codes: int8 [n], values in [-127, 127].  scales: fp32 [nb].
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; no entry point synchronises.
+ *   - Return value: an equarx_status.  A call that fails validation launches
+ *     nothing and touches no memory.  n == 0 is valid and does nothing;
+ *     n above 2^40 is EQUARX_BAD_SHAPE.
+ *   - Pointers must be 16-byte aligned (8-byte for codes, 4 for scales is not
+ *     enough: every data pointer is checked against 16).
+ *   - Supported block sizes: 32, 64, 128, 256, 512.
+ *   - NaN or infinite inputs give unspecified codes/scales but never a fault.
+ */
+#ifndef EQUARX_H
+#define EQUARX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum equarx_status {
+    EQUARX_OK = 0,
+    EQUARX_NULL_POINTER = 1,        /* a required pointer is NULL */
+    EQUARX_BAD_SHAPE = 2,           /* n < 0, P < 1, P > EQUARX_MAX_PARTIALS, or aliasing that is not allowed */
+    EQUARX_BAD_BLOCK = 3,           /* block not in {32, 64, 128, 256, 512} */
+    EQUARX_MISALIGNED = 4,          /* a data pointer is not 16-byte aligned */
+    EQUARX_WORKSPACE_TOO_SMALL = 5, /* workspace_bytes < equarx_workspace_bytes(...) */
+    EQUARX_DEVICE_ERROR = 6         /* the HIP runtime reported an error at launch */
+} equarx_status;
+
+#define EQUARX_MAX_PARTIALS 64
+
+/*
+ * Quantize a bf16 tensor block-wise to int8 (Sec. 3.2: symmetric, scale-only
+ * quantization whose scale comes from a max-abs reduction; Sec. 3.1: the
+ * first step of the reduce-scatter quantizes the shard before sending it).
+ *
+ * Per block: absmax = max |x|; scale = absmax / 127; codes =
+ * rne(x * (127 / absmax)) (round to nearest, ties to even), both quotients
+ * correctly rounded fp32.  absmax < 127 * 2^-126 gives scale 0, codes 0.
+ *
+ *   x_bf16 [n] in, codes [n] out, scales [nb] out.
+ */
+int equarx_quantize(const void *x_bf16, int64_t n, int32_t block,
+                    int8_t *codes, float *scales, void *stream);
+
+/*
+ * Dequantize int8 codes to bf16 (Sec. 3.4: the dequantize that ends a
+ * quantized all-gather).  out = bf16_rne(fp32(code) * scale[block of the
+ * element]).
+ *
+ *   codes [n] in, scales [nb] in, out_bf16 [n] out.
+ */
+int equarx_dequantize(const int8_t *codes, const float *scales, int64_t n, int32_t block,
+                      void *out_bf16, void *stream);
+
+/*
+ * One reduce-scatter step as the receiving device performs it (Sec. 3 and
+ * 3.1): dequantize the received shard to fp32, add the local -- unquantized --
+ * bf16 shard, quantize the partial sum for the next send.
+ *
+ *   t = fma(fp32(codes_in), scales_in[block], fp32(local))   (one rounding)
+ *   (codes_out, scales_out) = quantize(t) as in equarx_quantize.
+ *
+ * codes_out may alias codes_in and scales_out may alias scales_in (each block
+ * is read completely before it is written); no other aliasing is allowed.
+ */
+int equarx_reduce_stage(const int8_t *codes_in, const float *scales_in, const void *local_bf16,
+                        int64_t n, int32_t block,
+                        int8_t *codes_out, float *scales_out, void *stream);
+
+/*
+ * The whole adder chain of the full-loop variant with reduce-scatter and
+ * all-gather both quantized (Sec. 3.3 full-loop, Sec. 3.4), hop by hop:
+ *
+ *   (c0, s0) = quantize(x_0)
+ *   (ci, si) = reduce_stage(c(i-1), s(i-1), x_i)      i = 1 .. P-1
+ *   out      = dequantize(c(P-1), s(P-1))
+ *
+ * One kernel per line, P+1 launches; every wire buffer (ci, si) is written
+ * once and read once.  P == 1 gives out = dequantize(quantize(x_0)).
+ *
+ *   partials_bf16   HOST array of P device pointers, each to n bf16 values,
+ *                   in chain order; read before the call returns.
+ *   out_bf16 [n]    device, must not alias a partial.
+ *   workspace       device, at least equarx_workspace_bytes(P, n, block)
+ *                   bytes, 256-byte aligned; holds the two ping-pong wire
+ *                   buffers.  Not needed (may be NULL) when both wire_* are given.
+ *   wire_codes      NULL, or device int8 [P][equarx_wire_row_codes(n)]:
+ *                   receives the codes on the wire after every quantization
+ *                   (row i = c_i in its first n entries; rows are padded so
+ *                   that each starts 16-byte aligned).
+ *   wire_scales     NULL, or device fp32 [P][equarx_wire_row_scales(n, block)],
+ *                   row i = s_i in its first nb entries; must be given
+ *                   together with wire_codes.
+ */
+int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
+                            void *out_bf16, void *workspace, size_t workspace_bytes,
+                            int8_t *wire_codes, float *wire_scales, void *stream);
+
+/* Bytes of workspace equarx_reduce_quantized needs (0 for invalid arguments). */
+size_t equarx_workspace_bytes(int32_t P, int64_t n, int32_t block);
+
+/* Number of blocks, ceil(n / block) (0 for invalid arguments). */
+int64_t equarx_num_blocks(int64_t n, int32_t block);
+
+/* Row lengths (in elements) of the optional wire_codes / wire_scales arrays:
+ * n and nb rounded up to a multiple of 16 bytes. */
+int64_t equarx_wire_row_codes(int64_t n);
+int64_t equarx_wire_row_scales(int64_t n, int32_t block);
+
+/* Static, NUL-terminated description of a status code. */
+const char *equarx_status_string(int status);
+
+/* Plain 16-byte-vector device copy of `bytes` bytes (a multiple of 16, both
+ * pointers 16-byte aligned): the calibration kernel the benchmark uses to
+ * find the HBM bandwidth a streaming kernel can reach on this device. */
+int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
+
+/* Profiling aid.  The next kernel the calling thread launches through this
+ * library (whichever entry point launches it) carries the two hipEvent_t
+ * handles, passed as void*: after the stream has been synchronised,
+ * hipEventElapsedTime(start, stop) is that one kernel's execution time.
+ * The setting applies to exactly one launch; either handle may be NULL. */
+void equarx_time_next_launch(void *start_event, void *stop_event);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* EQUARX_H */

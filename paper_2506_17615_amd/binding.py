@@ -1,0 +1,183 @@
+"""Thin Python binding of libequarx.so: argument marshalling only.
+
+Every function has the name and meaning of the C entry point declared in
+``include/equarx.h``; tensors are torch CUDA tensors used purely as device
+memory, and work is enqueued on torch's current stream.  There is no CPU
+fallback: if the HIP library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+_lib = None
+
+STATUS_OK = 0
+STATUS_NULL_POINTER = 1
+STATUS_BAD_SHAPE = 2
+STATUS_BAD_BLOCK = 3
+STATUS_MISALIGNED = 4
+STATUS_WORKSPACE_TOO_SMALL = 5
+STATUS_DEVICE_ERROR = 6
+MAX_PARTIALS = 64
+BLOCK_SIZES = (32, 64, 128, 256, 512)
+
+# name -> (restype, argtypes); mirrors include/equarx.h
+_vp, _i64, _i32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+SIGNATURES = {
+    "equarx_quantize": (ctypes.c_int, [_vp, _i64, _i32, _vp, _vp, _vp]),
+    "equarx_dequantize": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp]),
+    "equarx_reduce_stage": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp]),
+    "equarx_reduce_quantized": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp, _vp, _vp]),
+    "equarx_workspace_bytes": (_sz, [_i32, _i64, _i32]),
+    "equarx_num_blocks": (_i64, [_i64, _i32]),
+    "equarx_wire_row_codes": (_i64, [_i64]),
+    "equarx_wire_row_scales": (_i64, [_i64, _i32]),
+    "equarx_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "equarx_calib_copy": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
+    "equarx_time_next_launch": (None, [_vp, _vp]),
+}
+
+
+class EquarxError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+def lib_path() -> str:
+    return _build.LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Open libequarx.so (built in-tree by ``build.build()``); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(
+                f"{path} is missing: build it first (python -m paper_2506_17615_amd.build); "
+                "there is no fallback path")
+        lib = ctypes.CDLL(path)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().equarx_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != STATUS_OK:
+        raise EquarxError(status, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _need(t, dtype, count: int, what: str) -> None:
+    """Host-side guard: a buffer handed to a kernel is a CUDA tensor of the right type, contiguous, long enough."""
+    if count == 0:
+        return
+    if t is None or not t.is_cuda or t.dtype != dtype or not t.is_contiguous() or t.numel() < count:
+        raise ValueError(f"{what}: need a contiguous CUDA {dtype} tensor of at least {count} elements")
+
+
+def num_blocks(n: int, block: int) -> int:
+    return int(load().equarx_num_blocks(n, block))
+
+
+def workspace_bytes(P: int, n: int, block: int) -> int:
+    return int(load().equarx_workspace_bytes(P, n, block))
+
+
+def wire_row_codes(n: int) -> int:
+    return int(load().equarx_wire_row_codes(n))
+
+
+def wire_row_scales(n: int, block: int) -> int:
+    return int(load().equarx_wire_row_scales(n, block))
+
+
+def equarx_quantize(x_bf16: torch.Tensor, block: int, codes: torch.Tensor, scales: torch.Tensor) -> None:
+    """codes[n] int8, scales[nb] fp32 <- Q_B(x_bf16[n])."""
+    n = x_bf16.numel()
+    _need(x_bf16, torch.bfloat16, n, "x_bf16")
+    _need(codes, torch.int8, n, "codes")
+    _need(scales, torch.float32, num_blocks(n, block), "scales")
+    _check(load().equarx_quantize(_ptr(x_bf16), x_bf16.numel(), block, _ptr(codes), _ptr(scales), _stream()),
+           "equarx_quantize")
+
+
+def equarx_dequantize(codes: torch.Tensor, scales: torch.Tensor, block: int, out_bf16: torch.Tensor) -> None:
+    """out_bf16[n] <- bf16(codes * scales[block])."""
+    n = codes.numel()
+    _need(codes, torch.int8, n, "codes")
+    _need(scales, torch.float32, num_blocks(n, block), "scales")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    _check(load().equarx_dequantize(_ptr(codes), _ptr(scales), codes.numel(), block, _ptr(out_bf16), _stream()),
+           "equarx_dequantize")
+
+
+def equarx_reduce_stage(codes_in, scales_in, local_bf16, block: int, codes_out, scales_out) -> None:
+    """One hop: (codes_out, scales_out) <- Q_B(fma(codes_in, scales_in, local_bf16))."""
+    n = local_bf16.numel()
+    nb = num_blocks(n, block)
+    _need(local_bf16, torch.bfloat16, n, "local_bf16")
+    _need(codes_in, torch.int8, n, "codes_in")
+    _need(codes_out, torch.int8, n, "codes_out")
+    _need(scales_in, torch.float32, nb, "scales_in")
+    _need(scales_out, torch.float32, nb, "scales_out")
+    _check(load().equarx_reduce_stage(_ptr(codes_in), _ptr(scales_in), _ptr(local_bf16), local_bf16.numel(), block,
+                                      _ptr(codes_out), _ptr(scales_out), _stream()), "equarx_reduce_stage")
+
+
+def equarx_reduce_quantized(partials, block: int, out_bf16, workspace=None, wire_codes=None, wire_scales=None) -> None:
+    """The whole chain over the partials (sequence of bf16 tensors of equal length, chain order)."""
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+        if p.numel() != n:
+            raise ValueError("partials differ in length")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    if wire_codes is not None or wire_scales is not None:
+        _need(wire_codes, torch.int8, P * wire_row_codes(n), "wire_codes")
+        _need(wire_scales, torch.float32, P * wire_row_scales(n, block) if block in BLOCK_SIZES else 0, "wire_scales")
+    if workspace is not None and not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace: need a contiguous CUDA tensor")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().equarx_reduce_quantized(table, P, n, block, _ptr(out_bf16), _ptr(workspace), ws_bytes,
+                                          _ptr(wire_codes), _ptr(wire_scales), _stream()), "equarx_reduce_quantized")
+
+
+def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+            and dst.numel() * dst.element_size() >= nbytes):
+        raise ValueError("calib_copy: need contiguous CUDA tensors, dst at least as large as src")
+    _check(load().equarx_calib_copy(_ptr(src), _ptr(dst), nbytes, _stream()), "equarx_calib_copy")
+
+
+def equarx_time_next_launch(start_event, stop_event) -> None:
+    """start/stop: raw hipEvent_t handles (ints); the next launch on this thread records its begin and end there."""
+    load().equarx_time_next_launch(start_event, stop_event)
+
+
+def alloc_workspace(P: int, n: int, block: int, device="cuda") -> torch.Tensor:
+    """Device buffer of the size the chain needs (torch is the allocator; the library never allocates)."""
+    return torch.empty(max(workspace_bytes(P, n, block), 256), dtype=torch.uint8, device=device)

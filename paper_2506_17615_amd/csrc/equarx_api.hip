@@ -1,0 +1,272 @@
+// Host side of libequarx: argument validation, kernel selection and launch.
+// The C ABI is declared and documented in include/equarx.h.
+#include "equarx.h"
+
+#include <hip/hip_ext.h>
+
+#include "equarx_device.hpp"
+
+namespace {
+
+using namespace equarx;
+
+constexpr size_t kAlign = 16;          // every data pointer
+constexpr size_t kWorkspaceAlign = 256;
+
+// Tiles a thread keeps in flight (K): 2048*K elements per workgroup.
+constexpr int kTilesQuantize = 2;
+constexpr int kTilesHop = 2;
+constexpr int kTilesDequantize = 2;
+
+inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+inline bool block_ok(int32_t block)
+{
+    return block == 32 || block == 64 || block == 128 || block == 256 || block == 512;
+}
+
+inline int64_t blocks_of(int64_t n, int32_t block) { return (n + block - 1) / block; }
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline unsigned grid_for(int64_t n, int tiles)
+{
+    const int64_t per_wg = (int64_t)kTileElems * tiles;
+    return (unsigned)((n + per_wg - 1) / per_wg);
+}
+
+// The grid is a 32-bit count of workgroups; 2048*K elements each.
+inline bool too_long(int64_t n) { return n > ((int64_t)1 << 40); }
+
+inline int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? EQUARX_OK : EQUARX_DEVICE_ERROR;
+}
+
+// Profiling aid (equarx_time_next_launch): events the calling thread's next
+// kernel launch carries, so that they record that kernel's own begin and end.
+thread_local hipEvent_t t_start_event = nullptr;
+thread_local hipEvent_t t_stop_event = nullptr;
+
+template <typename... KArgs, typename... Args>
+inline void launch(void (*kernel)(KArgs...), unsigned grid, hipStream_t s, Args... args)
+{
+    hipEvent_t e0 = t_start_event, e1 = t_stop_event;
+    t_start_event = nullptr;
+    t_stop_event = nullptr;
+    hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, s, e0, e1, 0, static_cast<KArgs>(args)...);
+}
+
+template <int B>
+void launch_quantize(const uint16_t *x, int64_t n, int8_t *codes, float *scales, hipStream_t s)
+{
+    launch(quantize_kernel<B, kTilesQuantize>, grid_for(n, kTilesQuantize), s, x, n, codes, scales, blocks_of(n, B));
+}
+
+template <int B>
+void launch_hop(const int8_t *cin, const float *sin, const uint16_t *x, int64_t n, int8_t *cout, float *sout,
+                hipStream_t s)
+{
+    launch(hop_kernel<B, kTilesHop>, grid_for(n, kTilesHop), s, cin, sin, x, n, cout, sout, blocks_of(n, B));
+}
+
+template <int B>
+void launch_dequantize(const int8_t *codes, const float *scales, int64_t n, uint16_t *out, hipStream_t s)
+{
+    launch(dequantize_kernel<B, kTilesDequantize>, grid_for(n, kTilesDequantize), s, codes, scales, n, out,
+           blocks_of(n, B));
+}
+
+#define EQUARX_DISPATCH_BLOCK(block, CALL)      \
+    switch (block) {                            \
+        case 32: CALL(32); break;               \
+        case 64: CALL(64); break;               \
+        case 128: CALL(128); break;             \
+        case 256: CALL(256); break;             \
+        case 512: CALL(512); break;             \
+        default: break;                         \
+    }
+
+void do_quantize(const void *x, int64_t n, int32_t block, int8_t *codes, float *scales, hipStream_t s)
+{
+#define CALL(BB) launch_quantize<BB>(static_cast<const uint16_t *>(x), n, codes, scales, s)
+    EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+}
+
+void do_hop(const int8_t *cin, const float *sin, const void *x, int64_t n, int32_t block, int8_t *cout, float *sout,
+            hipStream_t s)
+{
+#define CALL(BB) launch_hop<BB>(cin, sin, static_cast<const uint16_t *>(x), n, cout, sout, s)
+    EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+}
+
+void do_dequantize(const int8_t *codes, const float *scales, int64_t n, int32_t block, void *out, hipStream_t s)
+{
+#define CALL(BB) launch_dequantize<BB>(codes, scales, n, static_cast<uint16_t *>(out), s)
+    EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+}
+
+inline int check_shape(int64_t n, int32_t block)
+{
+    if (!block_ok(block)) return EQUARX_BAD_BLOCK;
+    if (n < 0 || too_long(n)) return EQUARX_BAD_SHAPE;
+    return EQUARX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t equarx_num_blocks(int64_t n, int32_t block)
+{
+    if (check_shape(n, block) != EQUARX_OK) return 0;
+    return blocks_of(n, block);
+}
+
+int64_t equarx_wire_row_codes(int64_t n)
+{
+    return n < 0 ? 0 : (int64_t)round_up((size_t)n, kAlign);
+}
+
+int64_t equarx_wire_row_scales(int64_t n, int32_t block)
+{
+    if (check_shape(n, block) != EQUARX_OK) return 0;
+    return (int64_t)round_up((size_t)blocks_of(n, block), kAlign / sizeof(float));
+}
+
+size_t equarx_workspace_bytes(int32_t P, int64_t n, int32_t block)
+{
+    if (P < 1 || P > EQUARX_MAX_PARTIALS || check_shape(n, block) != EQUARX_OK) return 0;
+    const size_t codes = round_up((size_t)n, kWorkspaceAlign);
+    const size_t scales = round_up((size_t)blocks_of(n, block) * sizeof(float), kWorkspaceAlign);
+    return 2 * (codes + scales);
+}
+
+const char *equarx_status_string(int status)
+{
+    switch (status) {
+        case EQUARX_OK: return "ok";
+        case EQUARX_NULL_POINTER: return "a required pointer is NULL";
+        case EQUARX_BAD_SHAPE: return "bad shape: n < 0, P out of range, or forbidden aliasing";
+        case EQUARX_BAD_BLOCK: return "block size must be 32, 64, 128, 256 or 512";
+        case EQUARX_MISALIGNED: return "a data pointer is not 16-byte aligned";
+        case EQUARX_WORKSPACE_TOO_SMALL: return "workspace is smaller than equarx_workspace_bytes()";
+        case EQUARX_DEVICE_ERROR: return "the HIP runtime reported an error at kernel launch";
+        default: return "unknown status";
+    }
+}
+
+int equarx_quantize(const void *x_bf16, int64_t n, int32_t block, int8_t *codes, float *scales, void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (n == 0) return EQUARX_OK;
+    if (!x_bf16 || !codes || !scales) return EQUARX_NULL_POINTER;
+    if (misaligned(x_bf16, kAlign) || misaligned(codes, kAlign) || misaligned(scales, kAlign)) return EQUARX_MISALIGNED;
+    do_quantize(x_bf16, n, block, codes, scales, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int equarx_dequantize(const int8_t *codes, const float *scales, int64_t n, int32_t block, void *out_bf16,
+                      void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (n == 0) return EQUARX_OK;
+    if (!codes || !scales || !out_bf16) return EQUARX_NULL_POINTER;
+    if (misaligned(codes, kAlign) || misaligned(scales, kAlign) || misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
+    do_dequantize(codes, scales, n, block, out_bf16, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int equarx_reduce_stage(const int8_t *codes_in, const float *scales_in, const void *local_bf16, int64_t n,
+                        int32_t block, int8_t *codes_out, float *scales_out, void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (n == 0) return EQUARX_OK;
+    if (!codes_in || !scales_in || !local_bf16 || !codes_out || !scales_out) return EQUARX_NULL_POINTER;
+    if (misaligned(codes_in, kAlign) || misaligned(scales_in, kAlign) || misaligned(local_bf16, kAlign) ||
+        misaligned(codes_out, kAlign) || misaligned(scales_out, kAlign))
+        return EQUARX_MISALIGNED;
+    do_hop(codes_in, scales_in, local_bf16, n, block, codes_out, scales_out, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block, void *out_bf16,
+                            void *workspace, size_t workspace_bytes, int8_t *wire_codes, float *wire_scales,
+                            void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16) return EQUARX_NULL_POINTER;
+    if ((wire_codes == nullptr) != (wire_scales == nullptr)) return EQUARX_NULL_POINTER;
+    const bool keep_wire = wire_codes != nullptr;
+    if (!keep_wire && !workspace) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
+    for (int32_t i = 0; i < P; ++i) {
+        if (!partials_bf16[i]) return EQUARX_NULL_POINTER;
+        if (misaligned(partials_bf16[i], kAlign)) return EQUARX_MISALIGNED;
+        if (partials_bf16[i] == out_bf16) return EQUARX_BAD_SHAPE;
+    }
+    const int64_t nb = blocks_of(n, block);
+    int8_t *c[2];
+    float *s[2];
+    int64_t c_step = 0, s_step = 0;     // distance between successive wire rows when they are kept
+    if (keep_wire) {
+        if (misaligned(wire_codes, kAlign) || misaligned(wire_scales, kAlign)) return EQUARX_MISALIGNED;
+        c_step = equarx_wire_row_codes(n);
+        s_step = equarx_wire_row_scales(n, block);
+        c[0] = wire_codes;
+        s[0] = wire_scales;
+        c[1] = nullptr;
+        s[1] = nullptr;
+    } else {
+        if (misaligned(workspace, kWorkspaceAlign)) return EQUARX_MISALIGNED;
+        if (workspace_bytes < equarx_workspace_bytes(P, n, block)) return EQUARX_WORKSPACE_TOO_SMALL;
+        const size_t codes = round_up((size_t)n, kWorkspaceAlign);
+        const size_t scales = round_up((size_t)nb * sizeof(float), kWorkspaceAlign);
+        char *w = static_cast<char *>(workspace);
+        c[0] = reinterpret_cast<int8_t *>(w);
+        s[0] = reinterpret_cast<float *>(w + codes);
+        c[1] = reinterpret_cast<int8_t *>(w + codes + scales);
+        s[1] = reinterpret_cast<float *>(w + 2 * codes + scales);
+    }
+
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int8_t *c_prev = c[0];
+    const float *s_prev = s[0];
+    do_quantize(partials_bf16[0], n, block, c[0], s[0], hs);
+    for (int32_t i = 1; i < P; ++i) {
+        int8_t *c_next = keep_wire ? wire_codes + i * c_step : c[i & 1];
+        float *s_next = keep_wire ? wire_scales + i * s_step : s[i & 1];
+        do_hop(c_prev, s_prev, partials_bf16[i], n, block, c_next, s_next, hs);
+        c_prev = c_next;
+        s_prev = s_next;
+    }
+    do_dequantize(c_prev, s_prev, n, block, out_bf16, hs);
+    return launch_status();
+}
+
+int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (bytes == 0) return EQUARX_OK;
+    if (!src || !dst) return EQUARX_NULL_POINTER;
+    if (bytes % 16 != 0) return EQUARX_BAD_SHAPE;
+    if (misaligned(src, kAlign) || misaligned(dst, kAlign)) return EQUARX_MISALIGNED;
+    const int64_t nvec = (int64_t)(bytes / 16);
+    const int64_t per_wg = kThreads * 4;
+    launch(copy_kernel, (unsigned)((nvec + per_wg - 1) / per_wg), static_cast<hipStream_t>(stream),
+           static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst), nvec);
+    return launch_status();
+}
+
+void equarx_time_next_launch(void *start_event, void *stop_event)
+{
+    t_start_event = static_cast<hipEvent_t>(start_event);
+    t_stop_event = static_cast<hipEvent_t>(stop_event);
+}
+
+}  // extern "C"

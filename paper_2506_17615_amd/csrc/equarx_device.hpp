@@ -1,0 +1,357 @@
+// Device code of libequarx: gfx950 (CDNA4, wave64) kernels for the block-wise
+// int8 quantized reduction of EQuARX (arXiv 2506.17615, Sec. 3.1-3.4).
+//
+// Work decomposition shared by all kernels
+//   lane   : owns 8 consecutive elements of a tile (one 16-byte bf16 load, one
+//            8-byte code load/store), so it sees the same elements in both
+//            streams;
+//   group  : the G = B/8 consecutive lanes that cover one quantization block
+//            (G = 4 .. 64, always inside one wavefront), reduced with DPP row
+//            operations and the gfx950 row-swap permutes;
+//   wave   : 512 consecutive elements per tile;
+//   block of 256 threads : 2048 consecutive elements per tile, K tiles per
+//            thread in flight, tile k of a workgroup starting 2048*k further.
+// Every load instruction of a workgroup therefore reads one contiguous 4 KiB
+// (bf16) or 2 KiB (codes) span.  Elements past n read as zero -- a zero never
+// changes a block's max-abs, so a ragged last block needs no special
+// arithmetic -- and are not stored.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace equarx {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte access
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));   // one 8-byte access
+
+constexpr int kLaneElems = 8;
+constexpr int kThreads = 256;
+constexpr int kTileElems = kThreads * kLaneElems;   // 2048 elements per workgroup tile
+
+// Smallest max-abs that still gets a non-zero scale: 127 * 2^-126, so that
+// scale = absmax/127 stays a normal number and 127/absmax stays finite.
+constexpr float kTinyAbsmax = 127.0f * 1.17549435e-38f;
+
+// ---------------------------------------------------------------- lane exchange
+
+template <int kCtrl>
+__device__ __forceinline__ uint32_t dpp_read(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kCtrl, 0xf, 0xf, false);
+}
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// Max over the G lanes of a group, result in every lane of the group.  The
+// operand is the bit pattern of a non-negative float, for which unsigned
+// integer order equals float order.  All 64 lanes of the wave must be active.
+template <int G>
+__device__ __forceinline__ uint32_t group_max_bits(uint32_t m)
+{
+    static_assert(G == 4 || G == 8 || G == 16 || G == 32 || G == 64, "group width");
+    m = umax(m, dpp_read<0xB1>(m));                 // quad_perm:[1,0,3,2]  lane ^ 1
+    m = umax(m, dpp_read<0x4E>(m));                 // quad_perm:[2,3,0,1]  lane ^ 2
+    if (G >= 8) m = umax(m, dpp_read<0x141>(m));    // row_half_mirror      the other quad of 8
+    if (G >= 16) m = umax(m, dpp_read<0x140>(m));   // row_mirror           the other half of 16
+    if (G >= 32) {                                  // rows 0<->1 and 2<->3 trade places
+        auto r = __builtin_amdgcn_permlane16_swap(m, m, false, false);
+        m = umax(r[0], r[1]);
+    }
+    if (G >= 64) {                                  // lower and upper 32 lanes trade places
+        auto r = __builtin_amdgcn_permlane32_swap(m, m, false, false);
+        m = umax(r[0], r[1]);
+    }
+    return m;
+}
+
+// ---------------------------------------------------------------- element codecs
+
+__device__ __forceinline__ void widen_bf16x8(const u32x4 &w, float (&f)[8])
+{
+    const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(d[i] << 16);
+        f[2 * i + 1] = __uint_as_float(d[i] & 0xFFFF0000u);
+    }
+}
+
+__device__ __forceinline__ void widen_i8x8(const u32x2 &w, float (&f)[8])
+{
+    const uint32_t d[2] = {w.x, w.y};
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            f[4 * i + b] = (float)(int)(int8_t)(d[i] >> (8 * b));
+        }
+    }
+}
+
+__device__ __forceinline__ uint32_t pack_i8x4(int a, int b, int c, int d)
+{
+    return (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) | ((uint32_t)d << 24);
+}
+
+__device__ __forceinline__ uint32_t narrow_bf16x2(float lo, float hi)
+{
+    // gfx950 converts in hardware (round to nearest, ties to even)
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float floatx2 __attribute__((ext_vector_type(2)));
+    floatx2 v = {lo, hi};
+    bf16x2 h = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// ---------------------------------------------------------------- guarded tile I/O
+// `full` is a compile-time constant at every call: the whole tile lies inside [0, n).
+
+__device__ __forceinline__ u32x4 load_bf16x8(const uint16_t *p, int64_t at, int64_t n, bool full)
+{
+    if (full || at + kLaneElems <= n) {
+        return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + at));
+    }
+    uint16_t e[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) e[i] = (at + i < n) ? p[at + i] : (uint16_t)0;
+    u32x4 w;
+    w.x = e[0] | ((uint32_t)e[1] << 16);
+    w.y = e[2] | ((uint32_t)e[3] << 16);
+    w.z = e[4] | ((uint32_t)e[5] << 16);
+    w.w = e[6] | ((uint32_t)e[7] << 16);
+    return w;
+}
+
+__device__ __forceinline__ u32x2 load_i8x8(const int8_t *p, int64_t at, int64_t n, bool full)
+{
+    if (full || at + kLaneElems <= n) {
+        return *reinterpret_cast<const u32x2 *>(p + at);
+    }
+    uint32_t e[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) e[i] = (at + i < n) ? (uint32_t)(uint8_t)p[at + i] : 0u;
+    u32x2 w;
+    w.x = e[0] | (e[1] << 8) | (e[2] << 16) | (e[3] << 24);
+    w.y = e[4] | (e[5] << 8) | (e[6] << 16) | (e[7] << 24);
+    return w;
+}
+
+__device__ __forceinline__ void store_i8x8(int8_t *p, int64_t at, int64_t n, bool full, const u32x2 &w)
+{
+    if (full || at + kLaneElems <= n) {
+        *reinterpret_cast<u32x2 *>(p + at) = w;
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (at + i < n) p[at + i] = (int8_t)(((i < 4 ? w.x : w.y) >> (8 * (i & 3))) & 0xFF);
+    }
+}
+
+__device__ __forceinline__ void store_bf16x8(uint16_t *p, int64_t at, int64_t n, bool full, const u32x4 &w)
+{
+    if (full || at + kLaneElems <= n) {
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(p + at));
+        return;
+    }
+    const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (at + i < n) p[at + i] = (uint16_t)(d[i >> 1] >> (16 * (i & 1)));
+    }
+}
+
+// ---------------------------------------------------------------- Q_B on registers
+
+// Quantize the 8 values a lane holds, given that the G lanes of its group hold
+// one block.  Returns the packed codes; `scale` is the block's scale (the same
+// in every lane of the group).
+template <int G>
+__device__ __forceinline__ u32x2 quantize_lane(const float (&t)[8], float &scale)
+{
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m = __builtin_fmaxf(m, __builtin_fabsf(t[i]));
+    const float a = __uint_as_float(group_max_bits<G>(__float_as_uint(m)));
+
+    float inv;
+    if (a < kTinyAbsmax) {
+        scale = 0.0f;
+        inv = 0.0f;
+    } else {
+        scale = a / 127.0f;     // correctly rounded divisions
+        inv = 127.0f / a;
+    }
+
+    int q[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        // |t*inv| <= 127*(1+2^-23): rounds to at most 127, no clamp needed
+        q[i] = (int)__builtin_rintf(t[i] * inv);
+    }
+    u32x2 w;
+    w.x = pack_i8x4(q[0], q[1], q[2], q[3]);
+    w.y = pack_i8x4(q[4], q[5], q[6], q[7]);
+    return w;
+}
+
+// ---------------------------------------------------------------- kernels
+// Each kernel body exists twice: kFull = true for workgroups whose K tiles lie
+// entirely inside [0, n) (straight-line vector code), kFull = false for the one
+// workgroup that holds the ragged end (every access guarded).
+
+template <int B, int K, bool kFull>
+__device__ __forceinline__ void quantize_body(const uint16_t *__restrict__ x, int64_t n, int8_t *__restrict__ codes,
+                                              float *__restrict__ scales, int64_t nb, int64_t wg_at)
+{
+    constexpr int G = B / kLaneElems;
+    const int lane_at = threadIdx.x * kLaneElems;
+
+    u32x4 xv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) xv[k] = load_bf16x8(x, wg_at + k * kTileElems + lane_at, n, kFull);
+
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        float t[8];
+        widen_bf16x8(xv[k], t);
+        float scale;
+        const u32x2 w = quantize_lane<G>(t, scale);
+        store_i8x8(codes, at, n, kFull, w);
+        const int64_t blk = at / B;
+        if ((threadIdx.x % G) == 0 && (kFull || blk < nb)) scales[blk] = scale;
+    }
+}
+
+// Pass 0 of the chain: quantize a bf16 tensor.
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__restrict__ x, int64_t n,
+                                                            int8_t *__restrict__ codes, float *__restrict__ scales,
+                                                            int64_t nb)
+{
+    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
+    if (wg_at + kTileElems * K <= n) {
+        quantize_body<B, K, true>(x, n, codes, scales, nb, wg_at);
+    } else {
+        quantize_body<B, K, false>(x, n, codes, scales, nb, wg_at);
+    }
+}
+
+template <int B, int K, bool kFull>
+__device__ __forceinline__ void hop_body(const int8_t *cin, const float *sin, const uint16_t *__restrict__ x,
+                                         int64_t n, int8_t *cout, float *sout, int64_t nb, int64_t wg_at)
+{
+    constexpr int G = B / kLaneElems;
+    const int lane_at = threadIdx.x * kLaneElems;
+
+    u32x4 xv[K];
+    u32x2 cv[K];
+    float sv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        xv[k] = load_bf16x8(x, at, n, kFull);
+        cv[k] = load_i8x8(cin, at, n, kFull);
+        const int64_t blk = at / B;
+        sv[k] = (kFull || blk < nb) ? sin[blk] : 0.0f;
+    }
+
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        float xf[8], qf[8], t[8];
+        widen_bf16x8(xv[k], xf);
+        widen_i8x8(cv[k], qf);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = __builtin_fmaf(qf[i], sv[k], xf[i]);
+        float scale;
+        const u32x2 w = quantize_lane<G>(t, scale);
+        store_i8x8(cout, at, n, kFull, w);
+        const int64_t blk = at / B;
+        if ((threadIdx.x % G) == 0 && (kFull || blk < nb)) sout[blk] = scale;
+    }
+}
+
+// One hop: dequantize the incoming wire, add the local bf16 shard in fp32
+// (one fused multiply-add per element), quantize the partial sum.  The output
+// wire may be the input wire: a thread reads its own elements, and a group its
+// own scale, before either is written.
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void hop_kernel(const int8_t *cin, const float *sin,
+                                                       const uint16_t *__restrict__ x, int64_t n,
+                                                       int8_t *cout, float *sout, int64_t nb)
+{
+    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
+    if (wg_at + kTileElems * K <= n) {
+        hop_body<B, K, true>(cin, sin, x, n, cout, sout, nb, wg_at);
+    } else {
+        hop_body<B, K, false>(cin, sin, x, n, cout, sout, nb, wg_at);
+    }
+}
+
+template <int B, int K, bool kFull>
+__device__ __forceinline__ void dequantize_body(const int8_t *__restrict__ codes, const float *__restrict__ scales,
+                                                int64_t n, uint16_t *__restrict__ out, int64_t nb, int64_t wg_at)
+{
+    const int lane_at = threadIdx.x * kLaneElems;
+
+    u32x2 cv[K];
+    float sv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        cv[k] = load_i8x8(codes, at, n, kFull);
+        const int64_t blk = at / B;
+        sv[k] = (kFull || blk < nb) ? scales[blk] : 0.0f;
+    }
+
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        float qf[8];
+        widen_i8x8(cv[k], qf);
+        u32x4 w;
+        w.x = narrow_bf16x2(qf[0] * sv[k], qf[1] * sv[k]);
+        w.y = narrow_bf16x2(qf[2] * sv[k], qf[3] * sv[k]);
+        w.z = narrow_bf16x2(qf[4] * sv[k], qf[5] * sv[k]);
+        w.w = narrow_bf16x2(qf[6] * sv[k], qf[7] * sv[k]);
+        store_bf16x8(out, at, n, kFull, w);
+    }
+}
+
+// Last pass: dequantize the wire to bf16.
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const int8_t *__restrict__ codes,
+                                                              const float *__restrict__ scales, int64_t n,
+                                                              uint16_t *__restrict__ out, int64_t nb)
+{
+    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
+    if (wg_at + kTileElems * K <= n) {
+        dequantize_body<B, K, true>(codes, scales, n, out, nb, wg_at);
+    } else {
+        dequantize_body<B, K, false>(codes, scales, n, out, nb, wg_at);
+    }
+}
+
+// Calibration: plain 16-byte-vector copy.
+__global__ __launch_bounds__(kThreads) void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+                                                        int64_t nvec)
+{
+    constexpr int K = 4;
+    const int64_t at = (int64_t)blockIdx.x * (kThreads * K) + threadIdx.x;
+    u32x4 v[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t i = at + k * kThreads;
+        if (i < nvec) v[k] = __builtin_nontemporal_load(src + i);
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t i = at + k * kThreads;
+        if (i < nvec) __builtin_nontemporal_store(v[k], dst + i);
+    }
+}
+
+}  // namespace equarx

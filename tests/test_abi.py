@@ -1,0 +1,121 @@
+"""The C-ABI library loads without a GPU, exports what include/equarx.h declares, and rejects bad arguments
+on the host (no kernel is launched by any call here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_17615_amd import binding, build
+
+HEADER = os.path.join(os.path.dirname(build.INCLUDE), "include", "equarx.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if build.is_stale():
+        build.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(equarx_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree(lib):
+    names = declared_functions()
+    assert "equarx_quantize" in names and "equarx_reduce_quantized" in names
+    assert set(names) == set(binding.SIGNATURES), "binding.SIGNATURES must list exactly the header's functions"
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in equarx.h but not exported"
+
+
+def test_status_strings(lib):
+    seen = {binding.status_string(s) for s in range(0, 7)}
+    assert len(seen) == 7 and "unknown status" not in seen
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_size_queries(lib):
+    assert binding.num_blocks(4096, 256) == 16
+    assert binding.num_blocks(4097, 256) == 17
+    assert binding.num_blocks(0, 32) == 0
+    assert binding.num_blocks(100, 100) == 0            # unsupported block
+    assert binding.num_blocks(-1, 32) == 0
+    assert binding.wire_row_codes(4097) == 4112 and binding.wire_row_scales(4097, 256) == 20
+    n, B = 22_020_096, 256
+    assert binding.workspace_bytes(8, n, B) == 2 * (n + 4 * n // B)
+    assert binding.workspace_bytes(8, 1000, 32) == 2 * (1024 + 256)
+    assert binding.workspace_bytes(0, n, B) == 0 and binding.workspace_bytes(65, n, B) == 0
+    assert binding.workspace_bytes(8, n, 48) == 0
+
+
+A = 0x7F0000001000          # a 16-byte aligned, never dereferenced address
+ODD = A + 8
+
+
+def test_validation_rejects_before_launch(lib):
+    q, d, st, rq = lib.equarx_quantize, lib.equarx_dequantize, lib.equarx_reduce_stage, lib.equarx_reduce_quantized
+    B = binding
+    # block sizes
+    for bad in (0, 1, 16, 48, 100, 1024, -256):
+        assert q(A, 4096, bad, A, A, None) == B.STATUS_BAD_BLOCK
+        assert d(A, A, 4096, bad, A, None) == B.STATUS_BAD_BLOCK
+        assert st(A, A, A, 4096, bad, A, A, None) == B.STATUS_BAD_BLOCK
+    # shapes
+    assert q(A, -1, 256, A, A, None) == B.STATUS_BAD_SHAPE
+    assert q(A, (1 << 40) + 1, 256, A, A, None) == B.STATUS_BAD_SHAPE
+    assert d(A, A, -5, 256, A, None) == B.STATUS_BAD_SHAPE
+    # n == 0 is a valid no-op, even with NULL buffers
+    assert q(None, 0, 256, None, None, None) == B.STATUS_OK
+    assert d(None, None, 0, 32, None, None) == B.STATUS_OK
+    assert st(None, None, None, 0, 64, None, None, None) == B.STATUS_OK
+    # NULL pointers
+    assert q(None, 4096, 256, A, A, None) == B.STATUS_NULL_POINTER
+    assert q(A, 4096, 256, None, A, None) == B.STATUS_NULL_POINTER
+    assert q(A, 4096, 256, A, None, None) == B.STATUS_NULL_POINTER
+    assert d(A, None, 4096, 256, A, None) == B.STATUS_NULL_POINTER
+    assert st(A, A, None, 4096, 256, A, A, None) == B.STATUS_NULL_POINTER
+    # alignment
+    assert q(ODD, 4096, 256, A, A, None) == B.STATUS_MISALIGNED
+    assert q(A, 4096, 256, ODD, A, None) == B.STATUS_MISALIGNED
+    assert q(A, 4096, 256, A, A + 4, None) == B.STATUS_MISALIGNED
+    assert d(A, A, 4096, 256, A + 2, None) == B.STATUS_MISALIGNED
+    assert st(A, A, ODD, 4096, 256, A, A, None) == B.STATUS_MISALIGNED
+
+    def table(*ptrs):
+        return (ctypes.c_void_p * len(ptrs))(*ptrs)
+
+    n, blk = 4096, 256
+    need = B.workspace_bytes(4, n, blk)
+    ok4 = table(A, A + 0x10000, A + 0x20000, A + 0x30000)
+    OUT, WS = A + 0x100000, A + 0x200000
+    assert rq(ok4, 0, n, blk, OUT, WS, need, None, None, None) == B.STATUS_BAD_SHAPE
+    assert rq(ok4, 65, n, blk, OUT, WS, need, None, None, None) == B.STATUS_BAD_SHAPE
+    assert rq(None, 4, n, blk, OUT, WS, need, None, None, None) == B.STATUS_NULL_POINTER
+    assert rq(ok4, 4, n, blk, None, WS, need, None, None, None) == B.STATUS_NULL_POINTER
+    assert rq(ok4, 4, n, blk, OUT, None, need, None, None, None) == B.STATUS_NULL_POINTER
+    assert rq(ok4, 4, n, blk, OUT, WS, need - 1, None, None, None) == B.STATUS_WORKSPACE_TOO_SMALL
+    assert rq(ok4, 4, n, blk, OUT, WS + 16, need, None, None, None) == B.STATUS_MISALIGNED
+    assert rq(table(A, 0, A, A), 4, n, blk, OUT, WS, need, None, None, None) == B.STATUS_NULL_POINTER
+    assert rq(table(A, A, ODD, A), 4, n, blk, OUT, WS, need, None, None, None) == B.STATUS_MISALIGNED
+    assert rq(table(A, OUT, A, A), 4, n, blk, OUT, WS, need, None, None, None) == B.STATUS_BAD_SHAPE   # out aliases a partial
+    assert rq(ok4, 4, n, blk, OUT, WS, need, A, None, None) == B.STATUS_NULL_POINTER                   # wire arrays come in pairs
+    assert rq(ok4, 4, n, blk, OUT, None, 0, ODD, A, None) == B.STATUS_MISALIGNED
+    assert rq(ok4, 4, n, 100, OUT, WS, need, None, None, None) == B.STATUS_BAD_BLOCK
+    assert rq(ok4, 4, 0, blk, None, None, 0, None, None, None) == B.STATUS_OK
+    # calibration copy
+    cp = lib.equarx_calib_copy
+    assert cp(A, A + 0x1000, 0, None) == B.STATUS_OK
+    assert cp(None, A, 64, None) == B.STATUS_NULL_POINTER
+    assert cp(A, A + 0x1000, 40, None) == B.STATUS_BAD_SHAPE
+    assert cp(A, ODD, 64, None) == B.STATUS_MISALIGNED
+
+
+def test_missing_library_is_an_error(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(build, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.load()

@@ -1,0 +1,222 @@
+"""GPU parity: every entry point of libequarx against the CPU oracle, element by element, on the same seeded inputs.
+
+Bar: int8 codes and fp32 scales bit-exact at every hop; the bf16 output bit-exact as well (the stated tolerance
+of one bf16 ulp, 2^-7 relative, is therefore met with room to spare and is asserted separately).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_17615_amd import binding as eq
+from paper_2506_17615_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+BLOCKS = (32, 64, 128, 256, 512)
+# lengths chosen against the kernel's geometry: 8 elements per lane, 512 per wave, 2048 per workgroup tile,
+# several tiles per workgroup -- whole tiles, a ragged last workgroup, a ragged last lane, a ragged last block
+LENGTHS = (4096, 1, 7, 8, 500, 2048 * 5, 2048 * 4 + 512 + 8 * 5 + 3, 2048 * 9 + 1024, 1 << 20, (1 << 20) + 136 + 5)
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _values(kind, n, seed):
+    rng = _rng(seed)
+    if kind == "normal":
+        v = rng.standard_normal(n)
+    elif kind == "lognormal":
+        v = rng.standard_normal(n) * np.exp(2 * rng.standard_normal(n))
+    elif kind == "student":
+        v = rng.standard_t(3, n)
+    elif kind == "tiny":          # straddles the zero-scale threshold and the subnormal range
+        v = rng.standard_normal(n) * 2.0 ** rng.integers(-136, -112, n)
+    elif kind == "huge":
+        v = rng.standard_normal(n) * 2.0 ** rng.integers(100, 124, n)
+    elif kind == "sparse":        # whole blocks of zeros, isolated spikes
+        v = rng.standard_normal(n) * (rng.random(n) < 0.02)
+        v[: min(n, 1024)] = 0
+    else:
+        raise ValueError(kind)
+    return v.astype(np.float32)
+
+
+KINDS = ("normal", "lognormal", "student", "tiny", "huge", "sparse")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import gpu_util
+    assert torch.cuda.is_available()
+    eq.load()
+    return gpu_util
+
+
+@pytest.mark.parametrize("B", BLOCKS)
+def test_quantize_parity(gpu, oracle, B):
+    for i, n in enumerate(LENGTHS):
+        for kind in KINDS if n <= 2048 * 9 + 1024 else ("normal", "tiny"):
+            x = gpu.bf16_of(_values(kind, n, 100 + i))
+            c, s = gpu.gpu_quantize(x, B)
+            co, so = oracle.quantize_bf16(x, B)
+            assert (c == co).all(), (B, n, kind, int((c != co).sum()))
+            assert (s.view(np.uint32) == so.view(np.uint32)).all(), (B, n, kind)
+
+
+@pytest.mark.parametrize("B", BLOCKS)
+def test_dequantize_parity(gpu, oracle, B):
+    for i, n in enumerate(LENGTHS):
+        rng = _rng(200 + i)
+        nb = oracle.num_blocks(n, B)
+        c = rng.integers(-127, 128, n).astype(np.int8)
+        s = (np.abs(rng.standard_normal(nb)) * 2.0 ** rng.integers(-130, 120, nb)).astype(np.float32)
+        out = gpu.gpu_dequantize(c, s, B)
+        assert (out == oracle.dequantize_bf16(c, s, B)).all(), (B, n)
+
+
+def test_dequantize_rounds_ties_to_even(gpu, oracle):
+    """code * scale values that sit exactly between two bf16 numbers."""
+    B = 32
+    c = np.tile(np.array([1, 3, 5, 7, -1, -3, -5, -7, 127, -127, 0, 2], np.int8), 64)[: 24 * B]
+    s = np.repeat(np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 2.0 ** -8, 255 / 256, 3.0 ** -40, 2.0 ** 100 * 1.00390625],
+                           np.float32), 4)
+    out = gpu.gpu_dequantize(c, s, B)
+    assert (out == oracle.dequantize_bf16(c, s, B)).all()
+
+
+@pytest.mark.parametrize("B", BLOCKS)
+def test_hop_parity(gpu, oracle, B):
+    for i, n in enumerate(LENGTHS):
+        for kind in ("normal", "lognormal", "tiny", "sparse") if n <= 2048 * 9 + 1024 else ("normal",):
+            rng = _rng(300 + i)
+            nb = oracle.num_blocks(n, B)
+            x = gpu.bf16_of(_values(kind, n, 400 + i))
+            cin = rng.integers(-127, 128, n).astype(np.int8)
+            mag = np.abs(oracle.bf16_to_f32(x)).max() + 1e-30
+            sin = (np.abs(rng.standard_normal(nb)) * mag / 100).astype(np.float32)
+            c, s = gpu.gpu_hop(cin, sin, x, B)
+            co, so = oracle.hop(cin, sin, x, B)
+            assert (c == co).all(), (B, n, kind, int((c != co).sum()))
+            assert (s.view(np.uint32) == so.view(np.uint32)).all(), (B, n, kind)
+
+
+def test_hop_in_place(gpu, oracle):
+    for B in (32, 256, 512):
+        n = 2048 * 7 + 640
+        rng = _rng(7)
+        x = gpu.bf16_of(_values("normal", n, 8))
+        cin = rng.integers(-127, 128, n).astype(np.int8)
+        sin = (np.abs(rng.standard_normal(oracle.num_blocks(n, B))) / 50).astype(np.float32)
+        c, s = gpu.gpu_hop(cin, sin, x, B, in_place=True)
+        co, so = oracle.hop(cin, sin, x, B)
+        assert (c == co).all() and (s == so).all()
+
+
+def _check_chain(gpu, oracle, parts, B):
+    out, wc, ws, _ = gpu.gpu_chain(parts, B)
+    oo, owc, ows = oracle.reduce_chain(parts, B, keep_wire=True)
+    for i in range(len(parts)):
+        assert (wc[i] == owc[i]).all(), ("codes differ at hop", i, int((wc[i] != owc[i]).sum()))
+        assert (ws[i].view(np.uint32) == ows[i].view(np.uint32)).all(), ("scales differ at hop", i)
+    assert (out == oo).all()
+    # the stated tolerance, 2^-7 relative (one bf16 ulp), holds a fortiori
+    a, b = oracle.bf16_to_f32(out).astype(np.float64), oracle.bf16_to_f32(oo).astype(np.float64)
+    assert (np.abs(a - b) <= 2.0 ** -7 * np.abs(b)).all()
+    # the same call without kept wire (ping-pong workspace) gives the same output
+    assert (gpu.gpu_chain(parts, B, keep_wire=False) == oo).all()
+
+
+CHAIN_CASES = {
+    "c1": wl.WORKLOADS["c1_small"],
+    "c2_rows24": wl.WORKLOADS["c2_gemma3_12b"].with_rows(24),
+    "c3_rows24": wl.WORKLOADS["c3_gemma3_27b"].with_rows(24),
+    "c4": wl.WORKLOADS["c4_decode"],
+}
+
+
+@pytest.mark.parametrize("case", sorted(CHAIN_CASES))
+def test_chain_parity_workloads(gpu, oracle, case):
+    w = CHAIN_CASES[case]
+    parts = [wl.as_u16(p) for p in wl.make_partials(w)]
+    _check_chain(gpu, oracle, parts, w.block)
+
+
+@pytest.mark.parametrize("B", (32, 128, 512))
+def test_chain_parity_heavy_tails(gpu, oracle, B):
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["c5_large"], hidden=(1 << 18) + 2048 + 40, block=B)
+    parts = [wl.as_u16(p) for p in wl.make_partials(w)]
+    _check_chain(gpu, oracle, parts, B)
+
+
+@pytest.mark.parametrize("P", (1, 2, 3, 64))
+def test_chain_lengths_of_chain(gpu, oracle, P):
+    n, B = 2048 * 3 + 300, 64
+    parts = [gpu.bf16_of(_values("lognormal", n, 500 + p)) for p in range(P)]
+    _check_chain(gpu, oracle, parts, B)
+
+
+def test_chain_degenerate_inputs(gpu, oracle):
+    n, B = 2048 * 2 + 77, 128
+    x = gpu.bf16_of(_values("normal", n, 1))
+    z = np.zeros(n, np.uint16)
+    _check_chain(gpu, oracle, [z, z, z], B)                       # all zero: scales 0, codes 0, output 0
+    _check_chain(gpu, oracle, [x, z, z, z], B)                    # requantizing the grid is idempotent
+    _check_chain(gpu, oracle, [x, x ^ np.uint16(0x8000)], B)      # cancellation down to the residual
+    _check_chain(gpu, oracle, [gpu.bf16_of(_values("tiny", n, 2)) for _ in range(4)], B)
+
+
+def test_empty_input_is_a_no_op(gpu):
+    e8 = torch.empty(0, dtype=torch.int8, device="cuda")
+    e32 = torch.empty(0, dtype=torch.float32, device="cuda")
+    e16 = torch.empty(0, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_quantize(e16, 256, e8, e32)
+    eq.equarx_dequantize(e8, e32, 256, e16)
+    eq.equarx_reduce_stage(e8, e32, e16, 256, e8, e32)
+    eq.equarx_reduce_quantized([e16, e16], 256, e16, None)
+    torch.cuda.synchronize()
+
+
+def test_non_finite_inputs_do_not_fault_and_stay_in_their_block(gpu, oracle):
+    """NaN/Inf results are unspecified, but blocks are independent: every block without one still matches."""
+    n, B = 2048 * 4, 256
+    v = _values("normal", n, 3)
+    v[5] = np.inf
+    v[B * 3 + 1] = np.nan
+    v[B * 9 + 200] = -np.inf
+    x = gpu.bf16_of(v)
+    y = gpu.bf16_of(_values("normal", n, 4))
+    out, wc, ws, _ = gpu.gpu_chain([x, y], B)
+    oo, owc, ows = oracle.reduce_chain([x, y], B, keep_wire=True)
+    clean = np.ones(n // B, bool)
+    clean[[0, 3, 9]] = False
+    keep = np.repeat(clean, B)
+    assert (out[keep] == oo[keep]).all() and (wc[:, keep] == owc[:, keep]).all() and (ws[:, clean] == ows[:, clean]).all()
+
+
+def test_bad_arguments_raise(gpu):
+    x = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(4096, dtype=torch.int8, device="cuda")
+    s = torch.zeros(16, dtype=torch.float32, device="cuda")
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_quantize(x, 100, c, s)
+    assert e.value.status == eq.STATUS_BAD_BLOCK
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_quantize(x[1:], 256, c, s)
+    assert e.value.status == eq.STATUS_MISALIGNED
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_quantized([x, x], 256, x, eq.alloc_workspace(2, 4096, 256))
+    assert e.value.status == eq.STATUS_BAD_SHAPE
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_quantized([x, x], 256, torch.empty_like(x), small)
+    assert e.value.status == eq.STATUS_WORKSPACE_TOO_SMALL
+
+
+def test_calibration_copy(gpu):
+    src = torch.randint(-128, 127, ((1 << 20) + 4096 + 16,), dtype=torch.int8, device="cuda")
+    dst = torch.zeros_like(src)
+    eq.equarx_calib_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
