@@ -220,3 +220,76 @@ def test_calibration_copy(gpu):
     eq.equarx_calib_copy(src, dst)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+
+
+# ----------------------------------------------------------------------------- full benchmark sizes
+
+def _sampled_blocks_check(gpu, oracle, w, n_sample=3000, seed=0):
+    """At full size, in the launch configuration bench.py times (workspace path), compare sampled blocks.
+
+    Blocks are independent of each other, so the oracle run on a gathered subset of blocks must reproduce the
+    GPU's values at exactly those blocks, bit for bit: output, and the codes and scales of every hop."""
+    host = wl.make_partials(w)
+    u16 = [wl.as_u16(p) for p in host]
+    n, B, P = w.n, w.block, w.P
+    nb = eq.num_blocks(n, B)
+    dev = [p.reshape(-1).cuda() for p in host]
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_quantized(dev, B, out, eq.alloc_workspace(P, n, B))
+    torch.cuda.synchronize()
+    out_h = gpu.host_u16(out)
+    rc, rs = eq.wire_row_codes(n), eq.wire_row_scales(n, B)
+    wc = torch.empty((P, rc), dtype=torch.int8, device="cuda")
+    ws = torch.empty((P, rs), dtype=torch.float32, device="cuda")
+    out2 = torch.empty_like(out)
+    eq.equarx_reduce_quantized(dev, B, out2, None, wc, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+
+    rng = _rng(seed)
+    blocks = np.unique(np.concatenate([[0, 1, nb - 2, nb - 1], rng.integers(0, nb, n_sample)]))
+    idx = (blocks[:, None] * B + np.arange(B)[None, :]).reshape(-1)
+    idx = idx[idx < n]
+    sub = [p[idx] for p in u16]
+    oo, owc, ows = oracle.reduce_chain(sub, B, keep_wire=True)
+    assert (out_h[idx] == oo).all()
+    idx_t = torch.from_numpy(idx).cuda()
+    blk_t = torch.from_numpy(blocks).cuda()
+    assert (wc[:, :n].index_select(1, idx_t).cpu().numpy() == owc).all()
+    assert (ws[:, :nb].index_select(1, blk_t).cpu().numpy().view(np.uint32) == ows.view(np.uint32)).all()
+
+    # properties that hold at any size, over the whole tensor: the codes use their range, every block's largest
+    # code is +-127 unless the block is all zero, and the output stays within the method's error bound
+    last = wc[-1, :n]
+    assert int(last.min()) >= -127
+    full = (n // B) * B
+    peak = last[:full].view(-1, B).abs().amax(dim=1)
+    zero_scale = ws[-1, : n // B] == 0
+    assert bool(((peak == 127) | zero_scale).all())
+    ref = torch.zeros(n, dtype=torch.float64, device="cuda")
+    for p in dev:
+        ref += p.double()
+    bound = ws[:, :nb].double().sum(dim=0).repeat_interleave(B)[:n] * 0.5 * (1 + 2.0 ** -10)
+    err = (out.double() - ref).abs()
+    # + the final bf16 rounding of the output (half an ulp: 2^-9 relative)
+    assert bool((err <= bound + ref.abs() * 2.0 ** -8 + 1e-30).all())
+
+
+def test_full_size_gemma3_27b_sampled(gpu, oracle):
+    _sampled_blocks_check(gpu, oracle, wl.WORKLOADS["c3_gemma3_27b"])
+
+
+def test_full_size_gemma3_12b_every_element(gpu, oracle):
+    w = wl.WORKLOADS["c2_gemma3_12b"]
+    u16 = [wl.as_u16(p) for p in wl.make_partials(w)]
+    oracle.set_threads(16)
+    try:
+        oo = oracle.reduce_chain(u16, w.block)
+    finally:
+        oracle.set_threads(1)
+    assert (gpu.gpu_chain(u16, w.block, keep_wire=False) == oo).all()
+
+
+@pytest.mark.parametrize("B", (32, 128, 512))
+def test_full_size_large_message_sampled(gpu, oracle, B):
+    _sampled_blocks_check(gpu, oracle, wl.WORKLOADS["c5_large"].with_block(B), n_sample=2000, seed=B)
