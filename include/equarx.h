@@ -115,6 +115,23 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
                             void *out_bf16, void *workspace, size_t workspace_bytes,
                             int8_t *wire_codes, float *wire_scales, void *stream);
 
+/*
+ * The same adder chain (Sec. 3.3 full-loop, Sec. 3.4) in ONE launch.  Blocks
+ * do not interact, so every workgroup runs all hops on its own tiles with the
+ * running codes and scale in registers: same operations, same order, same
+ * bits as equarx_reduce_quantized.  Each partial is read once; nothing
+ * intermediate is written unless the wire arrays are given, and the wire is
+ * never read back.  Needs no workspace.  On a single device this removes the
+ * P+1 launches and the 2(P-1) wire passes of the hop-by-hop schedule; it is
+ * not what a multi-device ring can do (there every hop's wire really crosses
+ * a link), which is why it is a separate entry point.
+ *
+ * Arguments as for equarx_reduce_quantized (wire_codes / wire_scales optional,
+ * same padded row layout).
+ */
+int equarx_reduce_fused(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
+                        void *out_bf16, int8_t *wire_codes, float *wire_scales, void *stream);
+
 /* Bytes of workspace equarx_reduce_quantized needs (0 for invalid arguments). */
 size_t equarx_workspace_bytes(int32_t P, int64_t n, int32_t block);
 

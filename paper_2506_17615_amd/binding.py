@@ -33,6 +33,7 @@ SIGNATURES = {
     "equarx_dequantize": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp]),
     "equarx_reduce_stage": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "equarx_reduce_quantized": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp, _vp, _vp]),
+    "equarx_reduce_fused": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp, _vp]),
     "equarx_workspace_bytes": (_sz, [_i32, _i64, _i32]),
     "equarx_num_blocks": (_i64, [_i64, _i32]),
     "equarx_wire_row_codes": (_i64, [_i64]),
@@ -163,6 +164,23 @@ def equarx_reduce_quantized(partials, block: int, out_bf16, workspace=None, wire
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().equarx_reduce_quantized(table, P, n, block, _ptr(out_bf16), _ptr(workspace), ws_bytes,
                                           _ptr(wire_codes), _ptr(wire_scales), _stream()), "equarx_reduce_quantized")
+
+
+def equarx_reduce_fused(partials, block: int, out_bf16, wire_codes=None, wire_scales=None) -> None:
+    """The whole chain in one launch (same bits as equarx_reduce_quantized, no workspace)."""
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+        if p.numel() != n:
+            raise ValueError("partials differ in length")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    if wire_codes is not None or wire_scales is not None:
+        _need(wire_codes, torch.int8, P * wire_row_codes(n), "wire_codes")
+        _need(wire_scales, torch.float32, P * wire_row_scales(n, block) if block in BLOCK_SIZES else 0, "wire_scales")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    _check(load().equarx_reduce_fused(table, P, n, block, _ptr(out_bf16), _ptr(wire_codes), _ptr(wire_scales),
+                                      _stream()), "equarx_reduce_fused")
 
 
 def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:

@@ -14,9 +14,19 @@ constexpr size_t kAlign = 16;          // every data pointer
 constexpr size_t kWorkspaceAlign = 256;
 
 // Tiles a thread keeps in flight (K): 2048*K elements per workgroup.
-constexpr int kTilesQuantize = 2;
-constexpr int kTilesHop = 2;
-constexpr int kTilesDequantize = 2;
+// Measured on MI355X at the 27B-shaped size: 3 beats 1, 2 and 4 by 2-5 %.
+#ifndef EQUARX_TILES_QUANTIZE
+#define EQUARX_TILES_QUANTIZE 3
+#endif
+#ifndef EQUARX_TILES_HOP
+#define EQUARX_TILES_HOP 3
+#endif
+#ifndef EQUARX_TILES_DEQUANTIZE
+#define EQUARX_TILES_DEQUANTIZE 3
+#endif
+constexpr int kTilesQuantize = EQUARX_TILES_QUANTIZE;
+constexpr int kTilesHop = EQUARX_TILES_HOP;
+constexpr int kTilesDequantize = EQUARX_TILES_DEQUANTIZE;
 
 inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
@@ -75,6 +85,26 @@ void launch_dequantize(const int8_t *codes, const float *scales, int64_t n, uint
 {
     launch(dequantize_kernel<B, kTilesDequantize>, grid_for(n, kTilesDequantize), s, codes, scales, n, out,
            blocks_of(n, B));
+}
+
+#ifndef EQUARX_TILES_CHAIN
+#define EQUARX_TILES_CHAIN 2
+#endif
+constexpr int kTilesChain = EQUARX_TILES_CHAIN;
+static_assert(kMaxPartials == EQUARX_MAX_PARTIALS, "header and device limit differ");
+
+template <int B>
+void launch_chain(const PartialTable &tab, int P, int64_t n, uint16_t *out, int8_t *wire_codes, float *wire_scales,
+                  int64_t c_step, int64_t s_step, hipStream_t s)
+{
+    const unsigned grid = grid_for(n, kTilesChain);
+    if (wire_codes) {
+        launch(chain_kernel<B, kTilesChain, true>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step,
+               blocks_of(n, B));
+    } else {
+        launch(chain_kernel<B, kTilesChain, false>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step,
+               blocks_of(n, B));
+    }
 }
 
 #define EQUARX_DISPATCH_BLOCK(block, CALL)      \
@@ -247,6 +277,34 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
         s_prev = s_next;
     }
     do_dequantize(c_prev, s_prev, n, block, out_bf16, hs);
+    return launch_status();
+}
+
+int equarx_reduce_fused(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block, void *out_bf16,
+                        int8_t *wire_codes, float *wire_scales, void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16) return EQUARX_NULL_POINTER;
+    if ((wire_codes == nullptr) != (wire_scales == nullptr)) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
+    if (wire_codes && (misaligned(wire_codes, kAlign) || misaligned(wire_scales, kAlign))) return EQUARX_MISALIGNED;
+    PartialTable tab;
+    for (int32_t i = 0; i < kMaxPartials; ++i) tab.x[i] = nullptr;
+    for (int32_t i = 0; i < P; ++i) {
+        if (!partials_bf16[i]) return EQUARX_NULL_POINTER;
+        if (misaligned(partials_bf16[i], kAlign)) return EQUARX_MISALIGNED;
+        if (partials_bf16[i] == out_bf16) return EQUARX_BAD_SHAPE;
+        tab.x[i] = static_cast<const uint16_t *>(partials_bf16[i]);
+    }
+    const int64_t c_step = equarx_wire_row_codes(n);
+    const int64_t s_step = equarx_wire_row_scales(n, block);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+#define CALL(BB) launch_chain<BB>(tab, P, n, static_cast<uint16_t *>(out_bf16), wire_codes, wire_scales, c_step, s_step, hs)
+    EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
     return launch_status();
 }
 

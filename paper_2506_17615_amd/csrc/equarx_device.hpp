@@ -25,8 +25,22 @@ namespace equarx {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte access
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));   // one 8-byte access
 
+// Build-time tuning knobs (defaults are what the library ships with).
+#ifndef EQUARX_THREADS
+#define EQUARX_THREADS 256          // threads per workgroup
+#endif
+#ifndef EQUARX_NT_LOAD_BF16
+#define EQUARX_NT_LOAD_BF16 1       // bf16 inputs are read once: non-temporal loads
+#endif
+#ifndef EQUARX_NT_STORE_BF16
+#define EQUARX_NT_STORE_BF16 1      // the bf16 output is not read again by this library
+#endif
+#ifndef EQUARX_NT_WIRE
+#define EQUARX_NT_WIRE 0            // the wire is re-read by the next hop: keep it cacheable
+#endif
+
 constexpr int kLaneElems = 8;
-constexpr int kThreads = 256;
+constexpr int kThreads = EQUARX_THREADS;
 constexpr int kTileElems = kThreads * kLaneElems;   // 2048 elements per workgroup tile
 
 // Smallest max-abs that still gets a non-zero scale: 127 * 2^-126, so that
@@ -110,7 +124,8 @@ __device__ __forceinline__ uint32_t narrow_bf16x2(float lo, float hi)
 __device__ __forceinline__ u32x4 load_bf16x8(const uint16_t *p, int64_t at, int64_t n, bool full)
 {
     if (full || at + kLaneElems <= n) {
-        return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + at));
+        const u32x4 *v = reinterpret_cast<const u32x4 *>(p + at);
+        return EQUARX_NT_LOAD_BF16 ? __builtin_nontemporal_load(v) : *v;
     }
     uint16_t e[8];
 #pragma unroll
@@ -126,7 +141,8 @@ __device__ __forceinline__ u32x4 load_bf16x8(const uint16_t *p, int64_t at, int6
 __device__ __forceinline__ u32x2 load_i8x8(const int8_t *p, int64_t at, int64_t n, bool full)
 {
     if (full || at + kLaneElems <= n) {
-        return *reinterpret_cast<const u32x2 *>(p + at);
+        const u32x2 *v = reinterpret_cast<const u32x2 *>(p + at);
+        return EQUARX_NT_WIRE ? __builtin_nontemporal_load(v) : *v;
     }
     uint32_t e[8];
 #pragma unroll
@@ -140,7 +156,12 @@ __device__ __forceinline__ u32x2 load_i8x8(const int8_t *p, int64_t at, int64_t 
 __device__ __forceinline__ void store_i8x8(int8_t *p, int64_t at, int64_t n, bool full, const u32x2 &w)
 {
     if (full || at + kLaneElems <= n) {
-        *reinterpret_cast<u32x2 *>(p + at) = w;
+        u32x2 *v = reinterpret_cast<u32x2 *>(p + at);
+        if (EQUARX_NT_WIRE) {
+            __builtin_nontemporal_store(w, v);
+        } else {
+            *v = w;
+        }
         return;
     }
 #pragma unroll
@@ -152,7 +173,12 @@ __device__ __forceinline__ void store_i8x8(int8_t *p, int64_t at, int64_t n, boo
 __device__ __forceinline__ void store_bf16x8(uint16_t *p, int64_t at, int64_t n, bool full, const u32x4 &w)
 {
     if (full || at + kLaneElems <= n) {
-        __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(p + at));
+        u32x4 *v = reinterpret_cast<u32x4 *>(p + at);
+        if (EQUARX_NT_STORE_BF16) {
+            __builtin_nontemporal_store(w, v);
+        } else {
+            *v = w;
+        }
         return;
     }
     const uint32_t d[4] = {w.x, w.y, w.z, w.w};
@@ -165,10 +191,10 @@ __device__ __forceinline__ void store_bf16x8(uint16_t *p, int64_t at, int64_t n,
 // ---------------------------------------------------------------- Q_B on registers
 
 // Quantize the 8 values a lane holds, given that the G lanes of its group hold
-// one block.  Returns the packed codes; `scale` is the block's scale (the same
-// in every lane of the group).
+// one block.  r[i] receives the code of t[i] as a float (an integer in
+// [-127, 127]); `scale` is the block's scale (the same in every lane of the group).
 template <int G>
-__device__ __forceinline__ u32x2 quantize_lane(const float (&t)[8], float &scale)
+__device__ __forceinline__ void quantize_lane_f(const float (&t)[8], float (&r)[8], float &scale)
 {
     float m = 0.0f;
 #pragma unroll
@@ -183,17 +209,28 @@ __device__ __forceinline__ u32x2 quantize_lane(const float (&t)[8], float &scale
         scale = a / 127.0f;     // correctly rounded divisions
         inv = 127.0f / a;
     }
-
-    int q[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         // |t*inv| <= 127*(1+2^-23): rounds to at most 127, no clamp needed
-        q[i] = (int)__builtin_rintf(t[i] * inv);
+        r[i] = __builtin_rintf(t[i] * inv);
     }
+}
+
+// The 8 float-valued codes of a lane as packed int8.
+__device__ __forceinline__ u32x2 pack_codes(const float (&r)[8])
+{
     u32x2 w;
-    w.x = pack_i8x4(q[0], q[1], q[2], q[3]);
-    w.y = pack_i8x4(q[4], q[5], q[6], q[7]);
+    w.x = pack_i8x4((int)r[0], (int)r[1], (int)r[2], (int)r[3]);
+    w.y = pack_i8x4((int)r[4], (int)r[5], (int)r[6], (int)r[7]);
     return w;
+}
+
+template <int G>
+__device__ __forceinline__ u32x2 quantize_lane(const float (&t)[8], float &scale)
+{
+    float r[8];
+    quantize_lane_f<G>(t, r, scale);
+    return pack_codes(r);
 }
 
 // ---------------------------------------------------------------- kernels
@@ -332,6 +369,109 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const int8_t *__re
         dequantize_body<B, K, true>(codes, scales, n, out, nb, wg_at);
     } else {
         dequantize_body<B, K, false>(codes, scales, n, out, nb, wg_at);
+    }
+}
+
+// ---------------------------------------------------------------- the whole chain in one launch
+// Blocks never interact, so a workgroup can run all P-1 hops on its own tiles
+// with the running codes and scale held in registers: the same operations in
+// the same order as the hop-by-hop passes, hence the same bits.  The partials
+// are read once each; the wire is written only if the caller keeps it (kWire)
+// and is never read back.
+
+constexpr int kMaxPartials = 64;
+
+struct PartialTable {
+    const uint16_t *x[kMaxPartials];
+};
+
+template <int B, int K, bool kWire, bool kFull>
+__device__ __forceinline__ void chain_body(const PartialTable &tab, int P, int64_t n, uint16_t *__restrict__ out,
+                                           int8_t *__restrict__ wire_codes, float *__restrict__ wire_scales,
+                                           int64_t c_step, int64_t s_step, int64_t nb, int64_t wg_at)
+{
+    constexpr int G = B / kLaneElems;
+    const int lane_at = threadIdx.x * kLaneElems;
+    const bool writes_scale = (threadIdx.x % G) == 0;
+
+    float r[K][8];      // running codes, as floats
+    float s[K];         // running scales
+    u32x4 xv[K];
+
+#pragma unroll
+    for (int k = 0; k < K; ++k) xv[k] = load_bf16x8(tab.x[0], wg_at + k * kTileElems + lane_at, n, kFull);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        float t[8];
+        widen_bf16x8(xv[k], t);
+        quantize_lane_f<G>(t, r[k], s[k]);
+    }
+    if (P > 1) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) xv[k] = load_bf16x8(tab.x[1], wg_at + k * kTileElems + lane_at, n, kFull);
+    }
+
+    for (int i = 1; i < P; ++i) {
+        if (kWire) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const int64_t at = wg_at + k * kTileElems + lane_at;
+                store_i8x8(wire_codes + (i - 1) * c_step, at, n, kFull, pack_codes(r[k]));
+                const int64_t blk = at / B;
+                if (writes_scale && (kFull || blk < nb)) wire_scales[(i - 1) * s_step + blk] = s[k];
+            }
+        }
+        u32x4 xc[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) xc[k] = xv[k];
+        if (i + 1 < P) {        // the next partial's loads fly while this hop computes
+#pragma unroll
+            for (int k = 0; k < K; ++k) xv[k] = load_bf16x8(tab.x[i + 1], wg_at + k * kTileElems + lane_at, n, kFull);
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            float xf[8], t[8];
+            widen_bf16x8(xc[k], xf);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(r[k][j], s[k], xf[j]);
+            quantize_lane_f<G>(t, r[k], s[k]);
+        }
+    }
+
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        if (kWire) {
+            store_i8x8(wire_codes + (int64_t)(P - 1) * c_step, at, n, kFull, pack_codes(r[k]));
+            const int64_t blk = at / B;
+            if (writes_scale && (kFull || blk < nb)) wire_scales[(int64_t)(P - 1) * s_step + blk] = s[k];
+        }
+        // A float-valued code can be -0.0 where the int8 code is plain 0; adding +0.0 turns it into the
+        // +0.0 an int8 -> float conversion gives (the sign of a zero is the only place the two could differ:
+        // |t|, the scales and the integer codes do not see it).
+        float d[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) d[j] = (r[k][j] + 0.0f) * s[k];
+        u32x4 w;
+        w.x = narrow_bf16x2(d[0], d[1]);
+        w.y = narrow_bf16x2(d[2], d[3]);
+        w.z = narrow_bf16x2(d[4], d[5]);
+        w.w = narrow_bf16x2(d[6], d[7]);
+        store_bf16x8(out, at, n, kFull, w);
+    }
+}
+
+template <int B, int K, bool kWire>
+__global__ __launch_bounds__(kThreads) void chain_kernel(const PartialTable tab, int P, int64_t n,
+                                                         uint16_t *__restrict__ out, int8_t *__restrict__ wire_codes,
+                                                         float *__restrict__ wire_scales, int64_t c_step,
+                                                         int64_t s_step, int64_t nb)
+{
+    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
+    if (wg_at + kTileElems * K <= n) {
+        chain_body<B, K, kWire, true>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, nb, wg_at);
+    } else {
+        chain_body<B, K, kWire, false>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, nb, wg_at);
     }
 }
 

@@ -69,3 +69,21 @@ def gpu_chain(partials_u16, B, keep_wire=True):
     eq.equarx_reduce_quantized(parts, B, out, work)
     torch.cuda.synchronize()
     return host_u16(out)
+
+
+def gpu_chain_fused(partials_u16, B, keep_wire=True):
+    """Runs equarx_reduce_fused (one launch); same returns as gpu_chain."""
+    parts = [dev_bf16(p) for p in partials_u16]
+    P, n = len(parts), parts[0].numel()
+    nb = eq.num_blocks(n, B)
+    out = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
+    if keep_wire:
+        rc, rs = eq.wire_row_codes(n), eq.wire_row_scales(n, B)
+        wc = torch.full((P, rc), 99, dtype=torch.int8, device="cuda")
+        ws = torch.full((P, rs), -7.0, dtype=torch.float32, device="cuda")
+        eq.equarx_reduce_fused(parts, B, out, wc, ws)
+        torch.cuda.synchronize()
+        return host_u16(out), wc[:, :n].cpu().numpy(), ws[:, :nb].cpu().numpy()
+    eq.equarx_reduce_fused(parts, B, out)
+    torch.cuda.synchronize()
+    return host_u16(out)

@@ -106,6 +106,20 @@ def test_validation_rejects_before_launch(lib):
     assert rq(ok4, 4, n, blk, OUT, None, 0, ODD, A, None) == B.STATUS_MISALIGNED
     assert rq(ok4, 4, n, 100, OUT, WS, need, None, None, None) == B.STATUS_BAD_BLOCK
     assert rq(ok4, 4, 0, blk, None, None, 0, None, None, None) == B.STATUS_OK
+    rf = lib.equarx_reduce_fused
+    assert rf(ok4, 0, n, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE
+    assert rf(ok4, 65, n, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE
+    assert rf(None, 4, n, blk, OUT, None, None, None) == B.STATUS_NULL_POINTER
+    assert rf(ok4, 4, n, blk, None, None, None, None) == B.STATUS_NULL_POINTER
+    assert rf(ok4, 4, n, blk, OUT, A, None, None) == B.STATUS_NULL_POINTER
+    assert rf(ok4, 4, n, blk, OUT + 2, None, None, None) == B.STATUS_MISALIGNED
+    assert rf(ok4, 4, n, blk, OUT, ODD, A, None) == B.STATUS_MISALIGNED
+    assert rf(table(A, A, 0, A), 4, n, blk, OUT, None, None, None) == B.STATUS_NULL_POINTER
+    assert rf(table(A, A, A, ODD), 4, n, blk, OUT, None, None, None) == B.STATUS_MISALIGNED
+    assert rf(table(OUT, A, A, A), 4, n, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE
+    assert rf(ok4, 4, n, 7, OUT, None, None, None) == B.STATUS_BAD_BLOCK
+    assert rf(ok4, 4, -3, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE
+    assert rf(ok4, 4, 0, blk, None, None, None, None) == B.STATUS_OK
     # calibration copy
     cp = lib.equarx_calib_copy
     assert cp(A, A + 0x1000, 0, None) == B.STATUS_OK

@@ -125,6 +125,10 @@ def _check_chain(gpu, oracle, parts, B):
     assert (np.abs(a - b) <= 2.0 ** -7 * np.abs(b)).all()
     # the same call without kept wire (ping-pong workspace) gives the same output
     assert (gpu.gpu_chain(parts, B, keep_wire=False) == oo).all()
+    # the single-launch chain: same bits, with and without the wire kept
+    fout, fwc, fws = gpu.gpu_chain_fused(parts, B)
+    assert (fout == oo).all() and (fwc == owc).all() and (fws.view(np.uint32) == ows.view(np.uint32)).all()
+    assert (gpu.gpu_chain_fused(parts, B, keep_wire=False) == oo).all()
 
 
 CHAIN_CASES = {
@@ -175,6 +179,7 @@ def test_empty_input_is_a_no_op(gpu):
     eq.equarx_dequantize(e8, e32, 256, e16)
     eq.equarx_reduce_stage(e8, e32, e16, 256, e8, e32)
     eq.equarx_reduce_quantized([e16, e16], 256, e16, None)
+    eq.equarx_reduce_fused([e16, e16], 256, e16)
     torch.cuda.synchronize()
 
 
@@ -208,6 +213,9 @@ def test_bad_arguments_raise(gpu):
     with pytest.raises(eq.EquarxError) as e:
         eq.equarx_reduce_quantized([x, x], 256, x, eq.alloc_workspace(2, 4096, 256))
     assert e.value.status == eq.STATUS_BAD_SHAPE
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_fused([x, x], 256, x)
+    assert e.value.status == eq.STATUS_BAD_SHAPE
     small = torch.empty(256, dtype=torch.uint8, device="cuda")
     with pytest.raises(eq.EquarxError) as e:
         eq.equarx_reduce_quantized([x, x], 256, torch.empty_like(x), small)
@@ -238,6 +246,10 @@ def _sampled_blocks_check(gpu, oracle, w, n_sample=3000, seed=0):
     eq.equarx_reduce_quantized(dev, B, out, eq.alloc_workspace(P, n, B))
     torch.cuda.synchronize()
     out_h = gpu.host_u16(out)
+    out_f = torch.empty_like(out)
+    eq.equarx_reduce_fused(dev, B, out_f)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out_f.view(torch.int16))      # single-launch chain, every element
     rc, rs = eq.wire_row_codes(n), eq.wire_row_scales(n, B)
     wc = torch.empty((P, rc), dtype=torch.int8, device="cuda")
     ws = torch.empty((P, rs), dtype=torch.float32, device="cuda")
