@@ -33,6 +33,11 @@ def chain_bytes(P: int, n: int, block: int) -> float:
     return n * (2.0 * P + 2.0 * P * (1.0 + 4.0 / block) + 2.0)
 
 
+def fused_bytes(P: int, n: int) -> float:
+    """Algorithmic bytes of the single-launch chain: every partial read once, the output written once."""
+    return n * (2.0 * P + 2.0)
+
+
 def read_traffic():
     """HBM bytes per hop launch from the committed rocprofv3 counter summary, or None."""
     try:
@@ -76,6 +81,9 @@ def main() -> int:
     ap.add_argument("--workload", default="c3_gemma3_27b")
     ap.add_argument("--block", type=int, default=0, help="override the workload's block size")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing; 0 skips it")
+    ap.add_argument("--schedule", choices=("hop", "fused"), default="hop",
+                    help="hop: P+1 launches, the wire written and read back (default, the schedule a ring imposes); "
+                         "fused: the same chain in one launch (equarx_reduce_fused)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all P partials live in one MI355X's HBM); "
@@ -113,10 +121,36 @@ def main() -> int:
             eq.equarx_reduce_quantized(sets[k % 2], B, out, work)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        ms_per_step = (t1 - t0) * 1e3 / K
+        hop_ms_per_step = (t1 - t0) * 1e3 / K
+
+        # the same chain in one launch: same bits, no wire traffic
+        for k in range(W):
+            eq.equarx_reduce_fused(sets[k % 2], B, out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(K):
+            eq.equarx_reduce_fused(sets[k % 2], B, out)
+        torch.cuda.synchronize()
+        fused_ms_per_step = (time.perf_counter() - t0) * 1e3 / K
+        fused_pairs = []
+        for _ in range(min(K, 50)):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            b.record(stream)
+            fused_pairs.append((a, b))
+        torch.cuda.synchronize()
+        for k, (a, b) in enumerate(fused_pairs):
+            eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
+            eq.equarx_reduce_fused(sets[k % 2], B, out)
+        torch.cuda.synchronize()
+        fused_kernel_ms = statistics.fmean(a.elapsed_time(b) for a, b in fused_pairs)
+        out_fused = out.clone()
 
         # error of the result against the exact sum (fp64), computed with torch on the GPU
+        eq.equarx_reduce_fused(sets[0], B, out_fused)
         eq.equarx_reduce_quantized(sets[0], B, out, work)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), out_fused.view(torch.int16)), "schedules disagree"
         ref = torch.zeros(n, dtype=torch.float64, device="cuda")
         for p in sets[0]:
             ref += p.double()
@@ -173,11 +207,37 @@ def main() -> int:
             cp.append(a.elapsed_time(b))
         copy_gbps = 2.0 * src.numel() / (statistics.median(cp) * 1e-3) / 1e9
 
-    dominant = "hop (dequantize + fp32 add + requantize)" if P > 1 else "quantize"
-    per_launch = hop_bytes(n, B) if P > 1 else n * (2.0 + 1.0 + 4.0 / B)
+    def gbps(nbytes, ms):
+        return nbytes / (ms * 1e-3) / 1e9
+
+    hop_info = {
+        "schedule": "hop-by-hop, P+1 launches, wire written once and read once",
+        "ms_per_step": round(hop_ms_per_step, 5),
+        "effective_input_GBps": round(gbps(2.0 * P * n, hop_ms_per_step), 1),
+        "algorithmic_bytes": chain_bytes(P, n, B),
+        "frac_of_hbm_peak": round(gbps(chain_bytes(P, n, B), hop_ms_per_step) / HBM_PEAK_GBPS, 4),
+    }
+    fused_info = {
+        "schedule": "single launch, chain in registers, no wire traffic",
+        "ms_per_step": round(fused_ms_per_step, 5),
+        "effective_input_GBps": round(gbps(2.0 * P * n, fused_ms_per_step), 1),
+        "algorithmic_bytes": fused_bytes(P, n),
+        "frac_of_hbm_peak": round(gbps(fused_bytes(P, n), fused_ms_per_step) / HBM_PEAK_GBPS, 4),
+        "kernel_avg_launch_us": round(fused_kernel_ms * 1e3, 3),
+    }
+    if args.schedule == "hop":
+        ms_per_step, chosen, other = hop_ms_per_step, hop_info, fused_info
+        dominant = "hop (dequantize + fp32 add + requantize)" if P > 1 else "quantize"
+        per_launch = hop_bytes(n, B) if P > 1 else n * (2.0 + 1.0 + 4.0 / B)
+        traffic = read_traffic() if (w.name, B) == ("c3_gemma3_27b", 256) else None
+    else:
+        ms_per_step, chosen, other = fused_ms_per_step, fused_info, hop_info
+        dominant = "chain (all hops in one launch)"
+        per_launch = fused_bytes(P, n)
+        kernel_ms, durs_ms = fused_kernel_ms, fused_pairs
+        traffic = None
     achieved = per_launch / (kernel_ms * 1e-3) / 1e9
     value = 2.0 * P * n / (ms_per_step * 1e-3) / 1e9
-    chain_frac = chain_bytes(P, n, B) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS
 
     result = {
         "metric": "effective input GB/s (bf16 bytes reduced/sec)",
@@ -193,10 +253,11 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "P": P, "rows": w.rows, "hidden": w.hidden, "n": n, "block": B,
-                   "distribution": w.dist, "schedule": "hop-by-hop, P+1 launches, wire written once and read once"},
-        "chain": {"algorithmic_bytes": chain_bytes(P, n, B), "frac_of_hbm_peak": round(chain_frac, 4)},
+                   "distribution": w.dist, "schedule": chosen["schedule"]},
+        "chain": chosen,
+        "other_schedule": other,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic(),
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": per_launch, "avg_launch_us": round(kernel_ms * 1e3, 3),
                      "launches_timed": len(durs_ms), "copy_kernel_GBps": round(copy_gbps, 1)},
         "error_vs_exact_sum": {"rel_l2": rel_l2, "mse": mse, "max_abs": max_abs},

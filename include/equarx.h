@@ -151,6 +151,27 @@ const char *equarx_status_string(int status);
  * find the HBM bandwidth a streaming kernel can reach on this device. */
 int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/*
+ * Self-tests of the kernels' arithmetic (used by the test suite).
+ *
+ * The quantizer needs, per block, scale = fl32(absmax / 127) and
+ * inv = fl32(127 / absmax), correctly rounded (Sec. 3.2 leaves the formula
+ * open; these are the readings the library documents).  The kernels compute
+ * them with short reciprocal-based sequences instead of a full IEEE division.
+ *
+ * equarx_selftest_quotients compares those sequences with the IEEE division on
+ * the device for the `count` consecutive fp32 bit patterns starting at
+ * first_bits (positive, finite: first_bits + count <= 0x7F800000) and ADDS the
+ * number of differing scales to mismatches[0] and of differing reciprocals to
+ * mismatches[1] (device pointer, two uint64, zeroed by the caller).
+ *
+ * equarx_eval_quotients evaluates them for n caller-given values (device
+ * arrays absmax[n] -> scale[n], inv[n]) so that a host can compare them with
+ * its own division.
+ */
+int equarx_selftest_quotients(uint32_t first_bits, uint64_t count, uint64_t *mismatches, void *stream);
+int equarx_eval_quotients(const float *absmax, int64_t n, float *scale, float *inv, void *stream);
+
 /* Profiling aid.  The next kernel the calling thread launches through this
  * library (whichever entry point launches it) carries the two hipEvent_t
  * handles, passed as void*: after the stream has been synchronised,

@@ -41,6 +41,8 @@ SIGNATURES = {
     "equarx_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "equarx_calib_copy": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
     "equarx_time_next_launch": (None, [_vp, _vp]),
+    "equarx_selftest_quotients": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint64, _vp, _vp]),
+    "equarx_eval_quotients": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp]),
 }
 
 
@@ -194,6 +196,20 @@ def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
 def equarx_time_next_launch(start_event, stop_event) -> None:
     """start/stop: raw hipEvent_t handles (ints); the next launch on this thread records its begin and end there."""
     load().equarx_time_next_launch(start_event, stop_event)
+
+
+def equarx_selftest_quotients(first_bits: int, count: int, mismatches: torch.Tensor) -> None:
+    """mismatches: CUDA int64[2], zeroed by the caller; receives the counts of differing scales / reciprocals."""
+    _need(mismatches, torch.int64, 2, "mismatches")
+    _check(load().equarx_selftest_quotients(first_bits, count, _ptr(mismatches), _stream()), "equarx_selftest_quotients")
+
+
+def equarx_eval_quotients(absmax: torch.Tensor, scale: torch.Tensor, inv: torch.Tensor) -> None:
+    n = absmax.numel()
+    _need(absmax, torch.float32, n, "absmax")
+    _need(scale, torch.float32, n, "scale")
+    _need(inv, torch.float32, n, "inv")
+    _check(load().equarx_eval_quotients(_ptr(absmax), n, _ptr(scale), _ptr(inv), _stream()), "equarx_eval_quotients")
 
 
 def alloc_workspace(P: int, n: int, block: int, device="cuda") -> torch.Tensor:

@@ -87,10 +87,16 @@ void launch_dequantize(const int8_t *codes, const float *scales, int64_t n, uint
            blocks_of(n, B));
 }
 
+// Single-launch chain, measured on MI355X (27B-shaped size): 4 tiles per thread and one partial of look-ahead
+// is fastest (62.7 us); deeper look-ahead (2..8 partials in flight) is 5-12 % slower, 1024-thread groups too.
 #ifndef EQUARX_TILES_CHAIN
-#define EQUARX_TILES_CHAIN 2
+#define EQUARX_TILES_CHAIN 4
+#endif
+#ifndef EQUARX_CHAIN_DEPTH
+#define EQUARX_CHAIN_DEPTH 1       // partials a thread keeps in flight in the single-launch chain
 #endif
 constexpr int kTilesChain = EQUARX_TILES_CHAIN;
+constexpr int kChainDepth = EQUARX_CHAIN_DEPTH;
 static_assert(kMaxPartials == EQUARX_MAX_PARTIALS, "header and device limit differ");
 
 template <int B>
@@ -99,10 +105,10 @@ void launch_chain(const PartialTable &tab, int P, int64_t n, uint16_t *out, int8
 {
     const unsigned grid = grid_for(n, kTilesChain);
     if (wire_codes) {
-        launch(chain_kernel<B, kTilesChain, true>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step,
+        launch(chain_kernel<B, kTilesChain, kChainDepth, true>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step,
                blocks_of(n, B));
     } else {
-        launch(chain_kernel<B, kTilesChain, false>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step,
+        launch(chain_kernel<B, kTilesChain, kChainDepth, false>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step,
                blocks_of(n, B));
     }
 }
@@ -318,6 +324,29 @@ int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream)
     const int64_t per_wg = kThreads * 4;
     launch(copy_kernel, (unsigned)((nvec + per_wg - 1) / per_wg), static_cast<hipStream_t>(stream),
            static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst), nvec);
+    return launch_status();
+}
+
+int equarx_selftest_quotients(uint32_t first_bits, uint64_t count, uint64_t *mismatches, void *stream)
+{
+    if (count == 0) return EQUARX_OK;
+    if (!mismatches) return EQUARX_NULL_POINTER;
+    if (misaligned(mismatches, 8)) return EQUARX_MISALIGNED;
+    if ((uint64_t)first_bits + count > 0x7F800000ull) return EQUARX_BAD_SHAPE;     // positive finite patterns only
+    const uint64_t wgs = (count + kThreads - 1) / kThreads;
+    launch(selftest_quotients_kernel, (unsigned)(wgs < 16384 ? wgs : 16384), static_cast<hipStream_t>(stream),
+           first_bits, count, reinterpret_cast<unsigned long long *>(mismatches));
+    return launch_status();
+}
+
+int equarx_eval_quotients(const float *absmax, int64_t n, float *scale, float *inv, void *stream)
+{
+    if (n < 0 || n > ((int64_t)1 << 31)) return EQUARX_BAD_SHAPE;
+    if (n == 0) return EQUARX_OK;
+    if (!absmax || !scale || !inv) return EQUARX_NULL_POINTER;
+    if (misaligned(absmax, 4) || misaligned(scale, 4) || misaligned(inv, 4)) return EQUARX_MISALIGNED;
+    launch(eval_quotients_kernel, (unsigned)((n + kThreads - 1) / kThreads), static_cast<hipStream_t>(stream), absmax, n,
+           scale, inv);
     return launch_status();
 }
 

@@ -188,6 +188,59 @@ __device__ __forceinline__ void store_bf16x8(uint16_t *p, int64_t at, int64_t n,
     }
 }
 
+// ---------------------------------------------------------------- the two quotients of a block
+
+// 127 / a is taken through the hardware reciprocal below this bound; from 2^126
+// on, 1/a is subnormal and the reciprocal is no longer accurate enough.
+constexpr float kRcpSafeBelow = 8.507059173e37f;    // 2^126
+
+// scale = fl32(a / 127) and inv = fl32(127 / a), both CORRECTLY ROUNDED, for a
+// block whose max-abs is a (scale = inv = 0 below the tiny threshold).
+//
+// The compiler's IEEE division costs about 11 instructions per quotient and
+// every lane of a group computes both, which is a third of the hop's ALU work.
+// These shorter sequences give the same bits:
+//   a / 127 : q0 = a*c with c = fl32(1/127), then one exact-remainder
+//             correction (the divisor is a constant whose reciprocal is known
+//             to half an ulp);
+//   127 / a : q0 = 127*rcp(a), then the same correction with the 1-ulp
+//             hardware reciprocal.
+// That they equal the IEEE quotient is not argued but CHECKED, exhaustively,
+// over every fp32 a in [127*2^-126, 2^126) -- selftest_quotients_kernel below,
+// run by the GPU tests -- and above 2^126 the IEEE division itself is used.
+__device__ __forceinline__ void block_quotients(float a, float &scale, float &inv)
+{
+    if (a < kTinyAbsmax) {
+        scale = 0.0f;
+        inv = 0.0f;
+        return;
+    }
+    const float c = 1.0f / 127.0f;                      // folded at compile time: fl32(1/127)
+    const float q0 = a * c;
+    const float e = __builtin_fmaf(-127.0f, q0, a);     // exact remainder a - 127*q0
+    scale = __builtin_fmaf(e, c, q0);
+    if (__builtin_expect(a < kRcpSafeBelow, 1)) {
+        const float y = __builtin_amdgcn_rcpf(a);
+        const float p0 = 127.0f * y;
+        const float r = __builtin_fmaf(-a, p0, 127.0f); // exact remainder 127 - a*p0
+        inv = __builtin_fmaf(r, y, p0);
+    } else {
+        inv = 127.0f / a;
+    }
+}
+
+// Reference form of the same two quotients: the compiler's IEEE division.
+__device__ __forceinline__ void block_quotients_ieee(float a, float &scale, float &inv)
+{
+    if (a < kTinyAbsmax) {
+        scale = 0.0f;
+        inv = 0.0f;
+    } else {
+        scale = a / 127.0f;
+        inv = 127.0f / a;
+    }
+}
+
 // ---------------------------------------------------------------- Q_B on registers
 
 // Quantize the 8 values a lane holds, given that the G lanes of its group hold
@@ -202,13 +255,7 @@ __device__ __forceinline__ void quantize_lane_f(const float (&t)[8], float (&r)[
     const float a = __uint_as_float(group_max_bits<G>(__float_as_uint(m)));
 
     float inv;
-    if (a < kTinyAbsmax) {
-        scale = 0.0f;
-        inv = 0.0f;
-    } else {
-        scale = a / 127.0f;     // correctly rounded divisions
-        inv = 127.0f / a;
-    }
+    block_quotients(a, scale, inv);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         // |t*inv| <= 127*(1+2^-23): rounds to at most 127, no clamp needed
@@ -385,7 +432,10 @@ struct PartialTable {
     const uint16_t *x[kMaxPartials];
 };
 
-template <int B, int K, bool kWire, bool kFull>
+// D = how many partials' tiles a thread keeps in flight: the loads of partial
+// i+D are issued when partial i is consumed, so that memory latency (a few
+// thousand cycles under load) is covered by D hops of arithmetic.
+template <int B, int K, int D, bool kWire, bool kFull>
 __device__ __forceinline__ void chain_body(const PartialTable &tab, int P, int64_t n, uint16_t *__restrict__ out,
                                            int8_t *__restrict__ wire_codes, float *__restrict__ wire_scales,
                                            int64_t c_step, int64_t s_step, int64_t nb, int64_t wg_at)
@@ -396,45 +446,60 @@ __device__ __forceinline__ void chain_body(const PartialTable &tab, int P, int64
 
     float r[K][8];      // running codes, as floats
     float s[K];         // running scales
-    u32x4 xv[K];
+    u32x4 buf[D][K];    // ring of loaded tiles: partial i sits in slot i % D
 
 #pragma unroll
-    for (int k = 0; k < K; ++k) xv[k] = load_bf16x8(tab.x[0], wg_at + k * kTileElems + lane_at, n, kFull);
+    for (int d = 0; d < D; ++d) {
+        if (d < P) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) buf[d][k] = load_bf16x8(tab.x[d], wg_at + k * kTileElems + lane_at, n, kFull);
+        }
+    }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         float t[8];
-        widen_bf16x8(xv[k], t);
+        widen_bf16x8(buf[0][k], t);
         quantize_lane_f<G>(t, r[k], s[k]);
     }
-    if (P > 1) {
+    if (D < P) {
 #pragma unroll
-        for (int k = 0; k < K; ++k) xv[k] = load_bf16x8(tab.x[1], wg_at + k * kTileElems + lane_at, n, kFull);
+        for (int k = 0; k < K; ++k) buf[0][k] = load_bf16x8(tab.x[D], wg_at + k * kTileElems + lane_at, n, kFull);
     }
 
-    for (int i = 1; i < P; ++i) {
-        if (kWire) {
+    for (int base = 1; base < P; base += D) {
 #pragma unroll
-            for (int k = 0; k < K; ++k) {
-                const int64_t at = wg_at + k * kTileElems + lane_at;
-                store_i8x8(wire_codes + (i - 1) * c_step, at, n, kFull, pack_codes(r[k]));
-                const int64_t blk = at / B;
-                if (writes_scale && (kFull || blk < nb)) wire_scales[(i - 1) * s_step + blk] = s[k];
+        for (int d = 0; d < D; ++d) {
+            const int i = base + d;             // i % D == (1 + d) % D: the slot is a compile-time constant
+            constexpr int kSlotBias = 1;
+            const int slot = (kSlotBias + d) % D;
+            if (i < P) {
+                if (kWire) {
+#pragma unroll
+                    for (int k = 0; k < K; ++k) {
+                        const int64_t at = wg_at + k * kTileElems + lane_at;
+                        store_i8x8(wire_codes + (i - 1) * c_step, at, n, kFull, pack_codes(r[k]));
+                        const int64_t blk = at / B;
+                        if (writes_scale && (kFull || blk < nb)) wire_scales[(i - 1) * s_step + blk] = s[k];
+                    }
+                }
+                u32x4 xc[K];
+#pragma unroll
+                for (int k = 0; k < K; ++k) xc[k] = buf[slot][k];
+                if (i + D < P) {
+#pragma unroll
+                    for (int k = 0; k < K; ++k) {
+                        buf[slot][k] = load_bf16x8(tab.x[i + D], wg_at + k * kTileElems + lane_at, n, kFull);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+                    float xf[8], t[8];
+                    widen_bf16x8(xc[k], xf);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(r[k][j], s[k], xf[j]);
+                    quantize_lane_f<G>(t, r[k], s[k]);
+                }
             }
-        }
-        u32x4 xc[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) xc[k] = xv[k];
-        if (i + 1 < P) {        // the next partial's loads fly while this hop computes
-#pragma unroll
-            for (int k = 0; k < K; ++k) xv[k] = load_bf16x8(tab.x[i + 1], wg_at + k * kTileElems + lane_at, n, kFull);
-        }
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            float xf[8], t[8];
-            widen_bf16x8(xc[k], xf);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(r[k][j], s[k], xf[j]);
-            quantize_lane_f<G>(t, r[k], s[k]);
         }
     }
 
@@ -461,7 +526,7 @@ __device__ __forceinline__ void chain_body(const PartialTable &tab, int P, int64
     }
 }
 
-template <int B, int K, bool kWire>
+template <int B, int K, int D, bool kWire>
 __global__ __launch_bounds__(kThreads) void chain_kernel(const PartialTable tab, int P, int64_t n,
                                                          uint16_t *__restrict__ out, int8_t *__restrict__ wire_codes,
                                                          float *__restrict__ wire_scales, int64_t c_step,
@@ -469,9 +534,45 @@ __global__ __launch_bounds__(kThreads) void chain_kernel(const PartialTable tab,
 {
     const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
     if (wg_at + kTileElems * K <= n) {
-        chain_body<B, K, kWire, true>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, nb, wg_at);
+        chain_body<B, K, D, kWire, true>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, nb, wg_at);
     } else {
-        chain_body<B, K, kWire, false>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, nb, wg_at);
+        chain_body<B, K, D, kWire, false>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, nb, wg_at);
+    }
+}
+
+// ---------------------------------------------------------------- self-tests of the arithmetic
+
+// Compares block_quotients with the IEEE division for the `count` consecutive
+// fp32 bit patterns starting at first_bits (grid-stride).  mismatches[0] counts
+// differing scales, mismatches[1] differing reciprocals.
+__global__ __launch_bounds__(kThreads) void selftest_quotients_kernel(uint32_t first_bits, uint64_t count,
+                                                                       unsigned long long *mismatches)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    unsigned bad_scale = 0, bad_inv = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const float a = __uint_as_float(first_bits + (uint32_t)i);
+        float s0, i0, s1, i1;
+        block_quotients(a, s0, i0);
+        block_quotients_ieee(a, s1, i1);
+        bad_scale += __float_as_uint(s0) != __float_as_uint(s1);
+        bad_inv += __float_as_uint(i0) != __float_as_uint(i1);
+    }
+    if (bad_scale) atomicAdd(&mismatches[0], (unsigned long long)bad_scale);
+    if (bad_inv) atomicAdd(&mismatches[1], (unsigned long long)bad_inv);
+}
+
+// Evaluates block_quotients on caller-chosen values, for comparison with a
+// division done on the host.
+__global__ __launch_bounds__(kThreads) void eval_quotients_kernel(const float *__restrict__ a, int64_t n,
+                                                                   float *__restrict__ scale, float *__restrict__ inv)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        float s, v;
+        block_quotients(a[i], s, v);
+        scale[i] = s;
+        inv[i] = v;
     }
 }
 

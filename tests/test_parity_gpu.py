@@ -305,3 +305,45 @@ def test_full_size_gemma3_12b_every_element(gpu, oracle):
 @pytest.mark.parametrize("B", (32, 128, 512))
 def test_full_size_large_message_sampled(gpu, oracle, B):
     _sampled_blocks_check(gpu, oracle, wl.WORKLOADS["c5_large"].with_block(B), n_sample=2000, seed=B)
+
+
+# ----------------------------------------------------------------------------- the kernels' own arithmetic
+
+def test_block_quotients_equal_ieee_division_for_every_fp32(gpu):
+    """The short reciprocal sequences the kernels use for absmax/127 and 127/absmax give the IEEE quotient for
+    EVERY fp32 absmax from the tiny threshold 127*2^-126 up to the largest finite value."""
+    bad = torch.zeros(2, dtype=torch.int64, device="cuda")
+    lo, hi = 0x03FE0000, 0x7F800000
+    step = 1 << 28
+    for first in range(lo, hi, step):
+        eq.equarx_selftest_quotients(first, min(step, hi - first), bad)
+    # below the threshold both forms give (0, 0)
+    eq.equarx_selftest_quotients(0, lo, bad)
+    torch.cuda.synchronize()
+    assert bad.tolist() == [0, 0]
+
+
+def test_block_quotients_equal_host_division(gpu):
+    """... and the host's IEEE division (numpy fp32) on random patterns, every bf16 value and the range edges."""
+    rng = _rng(77)
+    bits = rng.integers(0x03FE0000, 0x7F800000, 4_000_000, dtype=np.int64).astype(np.uint32)
+    bf = (np.arange(0x03FE, 0x7F80, dtype=np.uint32) << 16)
+    edges = np.array([0x03FE0000, 0x03FE0001, 0x7E7FFFFF, 0x7E800000, 0x7E800001, 0x7F7FFFFF, 0x3F800000, 0x42FE0000],
+                     np.uint32)
+    a = np.concatenate([bits, bf, edges]).view(np.float32)
+    d = torch.from_numpy(a).cuda()
+    s = torch.empty_like(d)
+    v = torch.empty_like(d)
+    eq.equarx_eval_quotients(d, s, v)
+    torch.cuda.synchronize()
+    with np.errstate(all="ignore"):
+        want_s = a / np.float32(127.0)
+        want_v = np.float32(127.0) / a
+    assert (s.cpu().numpy().view(np.uint32) == want_s.view(np.uint32)).all()
+    assert (v.cpu().numpy().view(np.uint32) == want_v.view(np.uint32)).all()
+    # below the threshold: zeros
+    tiny = torch.tensor([0.0, 1e-45, 1.17549435e-38, 1.4928e-36], device="cuda")
+    s2, v2 = torch.empty_like(tiny), torch.empty_like(tiny)
+    eq.equarx_eval_quotients(tiny, s2, v2)
+    torch.cuda.synchronize()
+    assert s2.tolist() == [0, 0, 0, 0] and v2.tolist() == [0, 0, 0, 0]
