@@ -280,3 +280,138 @@ void equarx_oracle_sum_f32(const uint16_t *const *partials, int32_t P, int64_t n
         ref[j] = acc;
     }
 }
+
+/* ======================================================================== *
+ * Variants of the chain (the paper's knobs and the forms a GPU mesh favours)
+ * ======================================================================== */
+
+/* Full-loop chain with the stage-selection knob (Sec. 3.4: the user picks
+ * whether the reduce-scatter stage, the all-gather stage, or both are
+ * quantized).
+ *   quantize_rs: what a device forwards during the reduce-scatter is quantized
+ *                (Sec. 3.1); otherwise partial sums travel and add in fp32.
+ *   quantize_ag: the finished sum is quantized once more for the all-gather
+ *                and dequantized by every receiver (Sec. 3.4); otherwise the
+ *                fp32 sum is narrowed to bf16 directly.
+ * The owner of a shard adds the last received partial sum to its own shard in
+ * fp32; that sum is not quantized by the reduce-scatter, only by the
+ * all-gather if that stage is quantized. */
+void equarx_oracle_reduce_stages(const uint16_t *const *partials, int32_t P, int64_t n, int32_t B,
+                                 int quantize_rs, int quantize_ag, uint16_t *out)
+{
+    int64_t nb = block_count(n, B);
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t b = 0; b < nb; ++b) {
+        int64_t len = block_len(n, B, b);
+        int64_t at = b * (int64_t)B;
+        float *t = (float *)malloc((size_t)len * sizeof(float));
+        int8_t *c = (int8_t *)malloc((size_t)len);
+        float s;
+
+        for (int64_t j = 0; j < len; ++j) t[j] = widen_bf16(partials[0][at + j]);
+        for (int32_t i = 1; i < P; ++i) {
+            if (quantize_rs) {
+                quantize_block(t, len, c, &s);                       /* sent to the next device */
+                for (int64_t j = 0; j < len; ++j) {
+                    t[j] = fmaf((float)c[j], s, widen_bf16(partials[i][at + j]));
+                }
+            } else {
+                for (int64_t j = 0; j < len; ++j) t[j] = t[j] + widen_bf16(partials[i][at + j]);
+            }
+        }
+        if (quantize_ag) {
+            quantize_block(t, len, c, &s);
+            for (int64_t j = 0; j < len; ++j) out[at + j] = narrow_bf16_rne((float)c[j] * s);
+        } else {
+            for (int64_t j = 0; j < len; ++j) out[at + j] = narrow_bf16_rne(t[j]);
+        }
+        free(t); free(c);
+    }
+}
+
+/* Semi-loop variant (Sec. 3.3): both ring directions are used and the owner
+ * of a shard (partials[0] here, the others in ring order around it) receives
+ * two partial sums.  With h = P/2:
+ *   clockwise chain          x_h -> x_(h-1) -> ... -> x_1 -> owner   (h sends)
+ *   counter-clockwise chain  x_(h+1) -> x_(h+2) -> ... -> x_(P-1) -> owner   (P-1-h sends)
+ * Every send is quantized; every receiver dequantizes and adds its own shard
+ * in fp32.  The shorter, counter-clockwise chain arrives first, so the owner
+ * adds it first (the paper's 4-device example: device 3's shard reaches
+ * device 0 in the first iteration, device 1's partial sum in the second).
+ * quantize_ag as in equarx_oracle_reduce_stages. */
+void equarx_oracle_reduce_semi_loop(const uint16_t *const *partials, int32_t P, int64_t n, int32_t B,
+                                    int quantize_ag, uint16_t *out)
+{
+    int64_t nb = block_count(n, B);
+    int32_t h = P / 2;
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t b = 0; b < nb; ++b) {
+        int64_t len = block_len(n, B, b);
+        int64_t at = b * (int64_t)B;
+        float *t = (float *)malloc((size_t)len * sizeof(float));
+        float *own = (float *)malloc((size_t)len * sizeof(float));
+        int8_t *c = (int8_t *)malloc((size_t)len);
+        float s;
+
+        for (int64_t j = 0; j < len; ++j) own[j] = widen_bf16(partials[0][at + j]);
+
+        if (h + 1 <= P - 1) {                      /* counter-clockwise: h+1, h+2, ..., P-1, then the owner */
+            for (int64_t j = 0; j < len; ++j) t[j] = widen_bf16(partials[h + 1][at + j]);
+            for (int32_t i = h + 2; i <= P - 1; ++i) {
+                quantize_block(t, len, c, &s);
+                for (int64_t j = 0; j < len; ++j) t[j] = fmaf((float)c[j], s, widen_bf16(partials[i][at + j]));
+            }
+            quantize_block(t, len, c, &s);
+            for (int64_t j = 0; j < len; ++j) own[j] = fmaf((float)c[j], s, own[j]);
+        }
+        if (h >= 1) {                              /* clockwise: h, h-1, ..., 1, then the owner */
+            for (int64_t j = 0; j < len; ++j) t[j] = widen_bf16(partials[h][at + j]);
+            for (int32_t i = h - 1; i >= 1; --i) {
+                quantize_block(t, len, c, &s);
+                for (int64_t j = 0; j < len; ++j) t[j] = fmaf((float)c[j], s, widen_bf16(partials[i][at + j]));
+            }
+            quantize_block(t, len, c, &s);
+            for (int64_t j = 0; j < len; ++j) own[j] = fmaf((float)c[j], s, own[j]);
+        }
+
+        if (quantize_ag) {
+            quantize_block(own, len, c, &s);
+            for (int64_t j = 0; j < len; ++j) out[at + j] = narrow_bf16_rne((float)c[j] * s);
+        } else {
+            for (int64_t j = 0; j < len; ++j) out[at + j] = narrow_bf16_rne(own[j]);
+        }
+        free(t); free(own); free(c);
+    }
+}
+
+/* Flat one-shot reduce: the reduce-scatter done as an all-to-all followed by a
+ * local reduction (the decomposition Sec. 2 describes for ZeRO++).  Every other
+ * device has quantized its shard once (Q_B, as in equarx_oracle_quantize_bf16)
+ * and the owner holds R received (codes, scales) pairs plus its own bf16
+ * shard.  It dequantizes and accumulates them in fp32, in array order, one
+ * fused multiply-add each, then quantizes the sum once for the all-gather.
+ *   codes[r], scales[r]: r = 0..R-1, each n codes / nb scales.
+ *   codes_out / scales_out (may be NULL): what the all-gather carries.
+ *   out: its dequantized bf16 value. */
+void equarx_oracle_reduce_flat(const uint16_t *local, const int8_t *const *codes, const float *const *scales,
+                               int32_t R, int64_t n, int32_t B, uint16_t *out, int8_t *codes_out, float *scales_out)
+{
+    int64_t nb = block_count(n, B);
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t b = 0; b < nb; ++b) {
+        int64_t len = block_len(n, B, b);
+        int64_t at = b * (int64_t)B;
+        float *acc = (float *)malloc((size_t)len * sizeof(float));
+        int8_t *c = (int8_t *)malloc((size_t)len);
+        float s;
+        for (int64_t j = 0; j < len; ++j) acc[j] = widen_bf16(local[at + j]);
+        for (int32_t r = 0; r < R; ++r) {
+            for (int64_t j = 0; j < len; ++j) acc[j] = fmaf((float)codes[r][at + j], scales[r][b], acc[j]);
+        }
+        quantize_block(acc, len, c, &s);
+        for (int64_t j = 0; j < len; ++j) out[at + j] = narrow_bf16_rne((float)c[j] * s);
+        if (codes_out) memcpy(codes_out + at, c, (size_t)len);
+        if (scales_out) scales_out[b] = s;
+        free(acc); free(c);
+    }
+}

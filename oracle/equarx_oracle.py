@@ -59,8 +59,13 @@ def _declare(lib: ctypes.CDLL) -> ctypes.CDLL:
     lib.equarx_oracle_reduce_chain.argtypes = [pp, i32, i64, i32, _c_u16p, _c_i8p, _c_f32p]
     lib.equarx_oracle_exact_sum_f64.argtypes = [pp, i32, i64, _c_f64p]
     lib.equarx_oracle_sum_f32.argtypes = [pp, i32, i64, _c_f32p]
+    lib.equarx_oracle_reduce_stages.argtypes = [pp, i32, i64, i32, ctypes.c_int, ctypes.c_int, _c_u16p]
+    lib.equarx_oracle_reduce_semi_loop.argtypes = [pp, i32, i64, i32, ctypes.c_int, _c_u16p]
+    lib.equarx_oracle_reduce_flat.argtypes = [_c_u16p, ctypes.POINTER(_c_i8p), ctypes.POINTER(_c_f32p), i32, i64, i32,
+                                              _c_u16p, _c_i8p, _c_f32p]
     for name in ("bf16_to_f32", "f32_to_bf16", "quantize_f32", "quantize_bf16", "dequantize_f32",
-                 "dequantize_bf16", "hop", "reduce_chain", "exact_sum_f64", "sum_f32"):
+                 "dequantize_bf16", "hop", "reduce_chain", "exact_sum_f64", "sum_f32", "reduce_stages",
+                 "reduce_semi_loop", "reduce_flat"):
         getattr(lib, "equarx_oracle_" + name).restype = None
     return lib
 
@@ -224,3 +229,69 @@ def sum_f32(partials, lib=None) -> np.ndarray:
     ref = np.empty(n, np.float32)
     (lib or _L()).equarx_oracle_sum_f32(table, len(arrs), n, _ptr(ref, _c_f32p))
     return ref
+
+
+def reduce_stages(partials, B: int, quantize_rs: bool = True, quantize_ag: bool = True, lib=None) -> np.ndarray:
+    """Full-loop chain with the stage knob: which of reduce-scatter / all-gather is quantized."""
+    B = _check_block(B)
+    arrs, table, n = _pointer_table(partials)
+    out = np.empty(n, np.uint16)
+    (lib or _L()).equarx_oracle_reduce_stages(table, len(arrs), n, B, int(bool(quantize_rs)), int(bool(quantize_ag)),
+                                              _ptr(out, _c_u16p))
+    return out
+
+
+def reduce_semi_loop(partials, B: int, quantize_ag: bool = True, lib=None) -> np.ndarray:
+    """Semi-loop chain: partials[0] is the owner, the others follow in ring order around it."""
+    B = _check_block(B)
+    arrs, table, n = _pointer_table(partials)
+    out = np.empty(n, np.uint16)
+    (lib or _L()).equarx_oracle_reduce_semi_loop(table, len(arrs), n, B, int(bool(quantize_ag)), _ptr(out, _c_u16p))
+    return out
+
+
+def reduce_flat(local_u16, codes_list, scales_list, B: int, lib=None):
+    """Flat one-shot reduce of a local bf16 shard and R received (codes, scales) pairs.
+
+    Returns (out bf16 [n], codes_out [n], scales_out [nb])."""
+    B = _check_block(B)
+    x = _arr(local_u16, np.uint16)
+    n = x.size
+    nb = num_blocks(n, B)
+    cs = [_arr(c, np.int8) for c in codes_list]
+    ss = [_arr(s, np.float32) for s in scales_list]
+    assert len(cs) == len(ss) and all(c.size == n for c in cs) and all(s.size == nb for s in ss)
+    R = len(cs)
+    ctab = (_c_i8p * max(R, 1))(*[_ptr(c, _c_i8p) for c in cs])
+    stab = (_c_f32p * max(R, 1))(*[_ptr(s, _c_f32p) for s in ss])
+    out = np.empty(n, np.uint16)
+    co = np.empty(n, np.int8)
+    so = np.empty(nb, np.float32)
+    (lib or _L()).equarx_oracle_reduce_flat(_ptr(x, _c_u16p), ctab, stab, R, n, B, _ptr(out, _c_u16p),
+                                            _ptr(co, _c_i8p), _ptr(so, _c_f32p))
+    return out, co, so
+
+
+def ring_order(P: int, shard: int):
+    """Order in which a ring reduce-scatter visits the devices for the shard that ends on device `shard`
+    (Sec. 3): the chain starts at the next device and walks once around the ring.  The direction is a
+    convention; the paper's figure is what would fix it."""
+    return [(shard + 1 + i) % P for i in range(P)]
+
+
+def shard_bounds(n: int, B: int, P: int):
+    """Split [0, n) into P shards on block boundaries: ceil(nb/P) blocks each, the last ones possibly short or empty."""
+    nb = num_blocks(n, B)
+    per = (nb + P - 1) // P
+    return [(min(n, k * per * B), min(n, (k + 1) * per * B)) for k in range(P)]
+
+
+def reduce_ring(partials, B: int, lib=None) -> np.ndarray:
+    """The chain as a real ring lays it out: shard k is reduced in the rotated order ring_order(P, k)."""
+    arrs = [_arr(p, np.uint16) for p in partials]
+    P, n = len(arrs), arrs[0].size
+    out = np.empty(n, np.uint16)
+    for k, (lo, hi) in enumerate(shard_bounds(n, B, P)):
+        if hi > lo:
+            out[lo:hi] = reduce_chain([arrs[d][lo:hi] for d in ring_order(P, k)], B, lib=lib)
+    return out

@@ -415,3 +415,171 @@ def pin_fig7_error(lib=None):
 ALL_PINS = [pin_zero_block, pin_absmax_to_127_all_bf16, pin_round_trip_half_scale, pin_special_blocks,
             pin_quantizer_exact_small, pin_dequantize, pin_bf16_narrowing, pin_hop_exact_small, pin_hop_special,
             pin_chain_error_bound, pin_chain_degenerate, pin_exact_sums, pin_fig7_error]
+
+
+# --------------------------------------------------------------------------- variants of the chain
+
+def _fma_exact(q, s, x):
+    """fl32(q*s + x) for fp32 arrays q, s, x, by exact rational arithmetic (small inputs only)."""
+    return np.array([round_to_f32(frac(a) * frac(b) + frac(c)) for a, b, c in zip(q, s, x)], np.float32)
+
+
+def _dq(c, s, B):
+    return c.astype(np.float32), np.repeat(s, B)[: c.size]
+
+
+def pin_stage_knobs(lib=None):
+    """The stage knob (Sec. 3.4): both = the pinned chain; none = an fp32 running sum cast by a library;
+    all-gather only = one Q/Dq of that sum; reduce-scatter only = the chain without its last quantization."""
+    for seed, P, n, B in ((1, 4, 3 * 256 + 100, 256), (2, 8, 640, 64), (3, 1, 300, 32), (4, 2, 512, 128)):
+        parts = _chain_inputs(100 + seed, P, n, heavy=bool(seed & 1))
+        assert (o.reduce_stages(parts, B, True, True, lib=lib) == o.reduce_chain(parts, B)).all()
+        acc = bf16_bits_to_f32(parts[0]).copy()
+        for p in parts[1:]:
+            acc = (acc + bf16_bits_to_f32(p)).astype(np.float32)
+        assert (o.reduce_stages(parts, B, False, False, lib=lib) == _bf16(acc)).all()
+        c, s = o.quantize_f32(acc, B)
+        assert (o.reduce_stages(parts, B, False, True, lib=lib) == o.dequantize_bf16(c, s, B)).all()
+        # reduce-scatter only: the wire before the last hop comes from the pinned chain; the owner's sum is
+        # fl32(q*s + x_last), checked exactly on a prefix
+        got = o.reduce_stages(parts, B, True, False, lib=lib)
+        if P == 1:
+            assert (got == parts[0]).all()
+        else:
+            _, wc, ws = o.reduce_chain(parts[:-1], B, keep_wire=True)
+            q, sc = _dq(wc[-1], ws[-1], B)
+            m = min(n, 200)
+            t = _fma_exact(q[:m], sc[:m], bf16_bits_to_f32(parts[-1])[:m])
+            assert (got[:m] == _bf16(t)).all()
+            # and over the whole tensor in fp64 (exact product, one rounding: at most an fp32 ulp off)
+            t64 = q.astype(np.float64) * sc.astype(np.float64) + bf16_bits_to_f32(parts[-1]).astype(np.float64)
+            back = bf16_bits_to_f32(got).astype(np.float64)
+            assert (np.abs(back - t64) <= np.abs(t64) * 2.0 ** -8 + 1e-30).all()
+
+
+def pin_semi_loop(lib=None):
+    """Semi-loop (Sec. 3.3): the paper's 4-device example written out with pinned primitives; P=1, P=2;
+    error bound; and lower error than the full loop."""
+    B, n = 64, 256
+    parts = _chain_inputs(7, 4, n)
+    x = [bf16_bits_to_f32(p) for p in parts]
+    # device 3 -> device 0 ; device 2 -> device 1 -> device 0 ; device 0 adds what arrives first, first
+    c3, s3 = o.quantize_bf16(parts[3], B)
+    own = _fma_exact(*_dq(c3, s3, B), x[0])
+    c2, s2 = o.quantize_bf16(parts[2], B)
+    t1 = _fma_exact(*_dq(c2, s2, B), x[1])
+    c1, s1 = o.quantize_f32(t1, B)
+    own = _fma_exact(*_dq(c1, s1, B), own)
+    assert (o.reduce_semi_loop(parts, B, quantize_ag=False, lib=lib) == _bf16(own)).all()
+    ca, sa = o.quantize_f32(own, B)
+    assert (o.reduce_semi_loop(parts, B, quantize_ag=True, lib=lib) == o.dequantize_bf16(ca, sa, B)).all()
+    # one device: nothing is sent; two devices: device 1 sends its quantized shard to the owner
+    assert (o.reduce_semi_loop(parts[:1], B, False, lib=lib) == parts[0]).all()
+    assert (o.reduce_semi_loop(parts[:1], B, True, lib=lib) == o.reduce_chain(parts[:1], B)).all()
+    assert (o.reduce_semi_loop(parts[:2], B, True, lib=lib) == o.reduce_chain([parts[1], parts[0]], B)).all()
+    # five devices (odd): chains 2 -> 1 -> owner and 3 -> 4 -> owner, the latter added first
+    parts5 = _chain_inputs(8, 5, n)
+    x5 = [bf16_bits_to_f32(p) for p in parts5]
+    c, s = o.quantize_bf16(parts5[3], B)
+    t = _fma_exact(*_dq(c, s, B), x5[4])
+    c, s = o.quantize_f32(t, B)
+    own = _fma_exact(*_dq(c, s, B), x5[0])
+    c, s = o.quantize_bf16(parts5[2], B)
+    t = _fma_exact(*_dq(c, s, B), x5[1])
+    c, s = o.quantize_f32(t, B)
+    own = _fma_exact(*_dq(c, s, B), own)
+    assert (o.reduce_semi_loop(parts5, B, False, lib=lib) == _bf16(own)).all()
+    # seven devices: counter-clockwise 4 -> 5 -> 6 -> owner, clockwise 3 -> 2 -> 1 -> owner
+    parts7 = _chain_inputs(10, 7, n)
+    x7 = [bf16_bits_to_f32(p) for p in parts7]
+
+    def sent_by(order):
+        c, s = o.quantize_bf16(parts7[order[0]], B)
+        for i in order[1:]:
+            c, s = o.quantize_f32(_fma_exact(*_dq(c, s, B), x7[i]), B)
+        return c, s
+
+    own = _fma_exact(*_dq(*sent_by([4, 5, 6]), B), x7[0])
+    own = _fma_exact(*_dq(*sent_by([3, 2, 1]), B), own)
+    assert (o.reduce_semi_loop(parts7, B, False, lib=lib) == _bf16(own)).all()
+    # every partial enters exactly once: exact sum within the accumulated half-steps
+    P, n2 = 8, 4096
+    parts8 = _chain_inputs(9, P, n2)
+    ref = sum(bf16_bits_to_f32(p).astype(np.float64) for p in parts8)
+    semi = bf16_bits_to_f32(o.reduce_semi_loop(parts8, B, True, lib=lib)).astype(np.float64)
+    assert np.abs(semi - ref).max() < 0.2 and np.abs(semi - ref).max() > 1e-3
+
+
+def pin_fig7_semi_loop(lib=None):
+    """Fig. 7: semi-loop with both stages quantized has MSE 0.001 (8 devices, block 64, N(0,1)), below the
+    full loop's 0.0014."""
+    g = read_golden("fig7_error.txt")
+    P, B = int(g["devices"]), int(g["block"])
+    n = 256 * 4096
+    parts = _chain_inputs(2024, P, n)
+    ref = np.zeros(n, np.float64)
+    for p in parts:
+        ref += bf16_bits_to_f32(p).astype(np.float64)
+    base = bf16_bits_to_f32(_bf16(ref.astype(np.float32))).astype(np.float64)
+    semi = bf16_bits_to_f32(o.reduce_semi_loop(parts, B, True, lib=lib)).astype(np.float64)
+    mse_semi = float(np.mean((semi - base) ** 2))
+    assert g["semi_loop_rs_ag"] / 1.5 <= mse_semi <= g["semi_loop_rs_ag"] * 1.5, mse_semi
+    full = bf16_bits_to_f32(o.reduce_chain(parts, B)).astype(np.float64)
+    assert mse_semi < float(np.mean((full - base) ** 2))
+    return mse_semi
+
+
+def pin_flat(lib=None):
+    """Flat one-shot reduce: one remote = a pinned hop + dequantize; accumulation order and single rounding
+    checked exactly on a small case; zero remotes = Q/Dq of the local shard."""
+    rng = _rng(91)
+    for B, n in ((32, 32 * 7 + 5), (256, 1024)):
+        nb = o.num_blocks(n, B)
+        local = _bf16(rng.standard_normal(n).astype(np.float32))
+        rem = [_bf16(rng.standard_normal(n).astype(np.float32)) for _ in range(3)]
+        qs = [o.quantize_bf16(r, B) for r in rem]
+        out, co, so = o.reduce_flat(local, [], [], B, lib=lib)
+        c0, s0 = o.quantize_bf16(local, B)
+        assert (co == c0).all() and (so == s0).all() and (out == o.dequantize_bf16(c0, s0, B)).all()
+        out, co, so = o.reduce_flat(local, [qs[0][0]], [qs[0][1]], B, lib=lib)
+        ch, sh = o.hop(qs[0][0], qs[0][1], local, B)
+        assert (co == ch).all() and (so == sh).all() and (out == o.dequantize_bf16(ch, sh, B)).all()
+        acc = bf16_bits_to_f32(local)
+        m = min(n, 160)
+        acc = acc[:m]
+        for c, s in qs:
+            q, sc = _dq(c, s, B)
+            acc = _fma_exact(q[:m], sc[:m], acc)
+        out, co, so = o.reduce_flat(local, [c for c, _ in qs], [s for _, s in qs], B, lib=lib)
+        full_blocks = (m // B) * B
+        ce, se = o.quantize_f32(acc[:full_blocks], B)
+        assert (co[:full_blocks] == ce).all() and (so[: full_blocks // B] == se).all()
+        assert (out[:full_blocks] == o.dequantize_bf16(ce, se, B)).all()
+        # two quantizations per value instead of P: the error stays within (sum of remote scales + own)/2
+        ref = bf16_bits_to_f32(local).astype(np.float64) + sum(bf16_bits_to_f32(r).astype(np.float64) for r in rem)
+        bound = (sum(np.repeat(s.astype(np.float64), B)[:n] for _, s in qs) + np.repeat(so.astype(np.float64), B)[:n]) * 0.5
+        err = np.abs(bf16_bits_to_f32(out).astype(np.float64) - ref)
+        assert (err <= bound * (1 + 2.0 ** -10) + np.abs(ref) * 2.0 ** -8).all()
+
+
+def pin_ring_order(lib=None):
+    """Ring layout: shard k is reduced in the order k+1, k+2, ..., k; with identical partials the order cannot
+    matter; with different ones each shard equals the chain run in its own rotated order."""
+    B, P = 32, 4
+    n = 32 * 10 + 7
+    rng = _rng(95)
+    same = _bf16(rng.standard_normal(n).astype(np.float32))
+    assert (o.reduce_ring([same] * P, B, lib=lib) == o.reduce_chain([same] * P, B)).all()
+    assert o.ring_order(4, 0) == [1, 2, 3, 0] and o.ring_order(4, 3) == [0, 1, 2, 3] and o.ring_order(1, 0) == [0]
+    bounds = o.shard_bounds(n, B, P)
+    assert bounds[0][0] == 0 and bounds[-1][1] == n and all(a[1] == b[0] for a, b in zip(bounds, bounds[1:]))
+    assert all(lo % B == 0 for lo, _ in bounds)
+    parts = _chain_inputs(96, P, n)
+    got = o.reduce_ring(parts, B, lib=lib)
+    lo, hi = bounds[3]
+    assert (got[lo:hi] == o.reduce_chain([p[lo:hi] for p in parts], B)).all()      # shard 3: natural order
+    lo, hi = bounds[1]
+    assert (got[lo:hi] == o.reduce_chain([parts[d][lo:hi] for d in (2, 3, 0, 1)], B)).all()
+
+
+ALL_PINS += [pin_stage_knobs, pin_semi_loop, pin_fig7_semi_loop, pin_flat, pin_ring_order]

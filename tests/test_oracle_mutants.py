@@ -43,6 +43,19 @@ MUTANTS = {
                                   "equarx_oracle_dequantize_bf16(c_next, s_next, n, B, out);"),
     "f32_sum_in_f64": ("for (int32_t i = 1; i < P; ++i) acc = acc + widen_bf16(partials[i][j]);",
                        "double a2 = acc; for (int32_t i = 1; i < P; ++i) a2 += widen_bf16(partials[i][j]); acc = (float)a2;"),
+    "stages_rs_off_uses_fma_path": ("t[j] = t[j] + widen_bf16(partials[i][at + j]);\n            }\n        }\n        if (quantize_ag)",
+                                    "t[j] = t[j] - widen_bf16(partials[i][at + j]);\n            }\n        }\n        if (quantize_ag)"),
+    "stages_always_quantizes_ag": ("        if (quantize_ag) {\n            quantize_block(t, len, c, &s);", "        if (1) {\n            quantize_block(t, len, c, &s);"),
+    "stages_ignores_rs_knob": ("            if (quantize_rs) {", "            if (1) {"),
+    "semi_wrong_half": ("    int32_t h = P / 2;", "    int32_t h = (P - 1) / 2;"),
+    "semi_cw_first": ("for (int64_t j = 0; j < len; ++j) own[j] = widen_bf16(partials[0][at + j]);",
+                      "for (int64_t j = 0; j < len; ++j) own[j] = widen_bf16(partials[0][at + j]);\n        if (h >= 1 && h + 1 <= P - 1) { for (int64_t j = 0; j < len; ++j) t[j] = widen_bf16(partials[h][at + j]); for (int32_t i = h - 1; i >= 1; --i) { quantize_block(t, len, c, &s); for (int64_t j = 0; j < len; ++j) t[j] = fmaf((float)c[j], s, widen_bf16(partials[i][at + j])); } quantize_block(t, len, c, &s); for (int64_t j = 0; j < len; ++j) own[j] = fmaf((float)c[j], s, own[j]); h = 0; }"),
+    "semi_ccw_walks_backwards": ("for (int32_t i = h + 2; i <= P - 1; ++i) {", "for (int32_t i = P - 1; i >= h + 2; --i) {"),
+    "semi_owner_quantized": ("for (int64_t j = 0; j < len; ++j) own[j] = widen_bf16(partials[0][at + j]);",
+                             "for (int64_t j = 0; j < len; ++j) own[j] = nearbyintf(widen_bf16(partials[0][at + j]) * 32.0f) / 32.0f;"),
+    "flat_unfused": ("acc[j] = fmaf((float)codes[r][at + j], scales[r][b], acc[j]);", "acc[j] = (float)codes[r][at + j] * scales[r][b] + acc[j];"),
+    "flat_wrong_scale_block": ("acc[j] = fmaf((float)codes[r][at + j], scales[r][b], acc[j]);", "acc[j] = fmaf((float)codes[r][at + j], scales[r][0], acc[j]);"),
+    "flat_skips_last_remote": ("for (int32_t r = 0; r < R; ++r) {", "for (int32_t r = 0; r + 1 < R || (R == 1 && r < 1); ++r) {"),
     "exact_sum_drops_last": ("for (int32_t i = 0; i < P; ++i) acc += (double)widen_bf16(partials[i][j]);",
                              "for (int32_t i = 0; i + 1 < P; ++i) acc += (double)widen_bf16(partials[i][j]);"),
 }
