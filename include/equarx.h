@@ -132,6 +132,42 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
 int equarx_reduce_fused(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
                         void *out_bf16, int8_t *wire_codes, float *wire_scales, void *stream);
 
+/*
+ * Variants of the chain, each in one launch (no wire kept).  `flags` is a
+ * combination of:
+ *
+ *   EQUARX_SEMI_LOOP       the semi-loop reduce-scatter of Sec. 3.3 instead of
+ *                          the full loop: partials[0] owns the result, the
+ *                          other partials follow in ring order around it; with
+ *                          h = P/2 the chains h+1 -> h+2 -> ... -> P-1 and
+ *                          h -> h-1 -> ... -> 1 each end in a quantized send to
+ *                          the owner, which adds them to its own fp32 shard
+ *                          (the shorter chain first).  Fewer requantizations
+ *                          of smaller partial sums: lower error.
+ *   EQUARX_RS_UNQUANTIZED  the stage knob of Sec. 3.4: the reduce-scatter adds
+ *                          in plain fp32 (array order), only the all-gather
+ *                          is quantized.  Not combinable with SEMI_LOOP.
+ *   EQUARX_AG_UNQUANTIZED  the all-gather is not quantized: the owner's fp32
+ *                          sum (last received wire dequantized + own shard)
+ *                          is narrowed to bf16 directly.  Setting both
+ *                          *_UNQUANTIZED flags is EQUARX_BAD_SHAPE.
+ *   EQUARX_RING_ORDER      lay the reduction out as a ring does (Sec. 3): the
+ *                          tensor is cut into P shards of ceil(nb/P) blocks,
+ *                          shard k ends on device k and is reduced in the
+ *                          order k+1, k+2, ..., k (full loop) or with device k
+ *                          as the semi-loop owner and k+1, k+2, ... around it.
+ *                          Without the flag every element uses array order.
+ *
+ * flags == 0 is equarx_reduce_fused without kept wire.  Other arguments as for
+ * equarx_reduce_fused.
+ */
+#define EQUARX_SEMI_LOOP 1u
+#define EQUARX_RS_UNQUANTIZED 2u
+#define EQUARX_AG_UNQUANTIZED 4u
+#define EQUARX_RING_ORDER 8u
+int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block, uint32_t flags,
+                          void *out_bf16, void *stream);
+
 /* Bytes of workspace equarx_reduce_quantized needs (0 for invalid arguments). */
 size_t equarx_workspace_bytes(int32_t P, int64_t n, int32_t block);
 

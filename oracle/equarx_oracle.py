@@ -286,12 +286,21 @@ def shard_bounds(n: int, B: int, P: int):
     return [(min(n, k * per * B), min(n, (k + 1) * per * B)) for k in range(P)]
 
 
-def reduce_ring(partials, B: int, lib=None) -> np.ndarray:
-    """The chain as a real ring lays it out: shard k is reduced in the rotated order ring_order(P, k)."""
+def reduce_ring(partials, B: int, semi: bool = False, quantize_rs: bool = True, quantize_ag: bool = True,
+                lib=None) -> np.ndarray:
+    """The reduction as a real ring lays it out: shard k ends on device k.
+
+    Full loop: shard k is reduced in the rotated order ring_order(P, k).  Semi-loop: device k is the owner
+    and the devices k+1, k+2, ... follow in ring order around it."""
     arrs = [_arr(p, np.uint16) for p in partials]
     P, n = len(arrs), arrs[0].size
     out = np.empty(n, np.uint16)
     for k, (lo, hi) in enumerate(shard_bounds(n, B, P)):
-        if hi > lo:
-            out[lo:hi] = reduce_chain([arrs[d][lo:hi] for d in ring_order(P, k)], B, lib=lib)
+        if hi <= lo:
+            continue
+        if semi:
+            order = [(k + j) % P for j in range(P)]
+            out[lo:hi] = reduce_semi_loop([arrs[d][lo:hi] for d in order], B, quantize_ag, lib=lib)
+        else:
+            out[lo:hi] = reduce_stages([arrs[d][lo:hi] for d in ring_order(P, k)], B, quantize_rs, quantize_ag, lib=lib)
     return out

@@ -25,6 +25,7 @@ STATUS_WORKSPACE_TOO_SMALL = 5
 STATUS_DEVICE_ERROR = 6
 MAX_PARTIALS = 64
 BLOCK_SIZES = (32, 64, 128, 256, 512)
+SEMI_LOOP, RS_UNQUANTIZED, AG_UNQUANTIZED, RING_ORDER = 1, 2, 4, 8
 
 # name -> (restype, argtypes); mirrors include/equarx.h
 _vp, _i64, _i32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
@@ -34,6 +35,7 @@ SIGNATURES = {
     "equarx_reduce_stage": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "equarx_reduce_quantized": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp, _vp, _vp]),
     "equarx_reduce_fused": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp, _vp]),
+    "equarx_reduce_variant": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp]),
     "equarx_workspace_bytes": (_sz, [_i32, _i64, _i32]),
     "equarx_num_blocks": (_i64, [_i64, _i32]),
     "equarx_wire_row_codes": (_i64, [_i64]),
@@ -183,6 +185,19 @@ def equarx_reduce_fused(partials, block: int, out_bf16, wire_codes=None, wire_sc
     table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
     _check(load().equarx_reduce_fused(table, P, n, block, _ptr(out_bf16), _ptr(wire_codes), _ptr(wire_scales),
                                       _stream()), "equarx_reduce_fused")
+
+
+def equarx_reduce_variant(partials, block: int, flags: int, out_bf16) -> None:
+    """A variant of the chain in one launch; flags: SEMI_LOOP | RS_UNQUANTIZED | AG_UNQUANTIZED | RING_ORDER."""
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+        if p.numel() != n:
+            raise ValueError("partials differ in length")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    _check(load().equarx_reduce_variant(table, P, n, block, flags, _ptr(out_bf16), _stream()), "equarx_reduce_variant")
 
 
 def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:

@@ -59,12 +59,18 @@ thread_local hipEvent_t t_start_event = nullptr;
 thread_local hipEvent_t t_stop_event = nullptr;
 
 template <typename... KArgs, typename... Args>
-inline void launch(void (*kernel)(KArgs...), unsigned grid, hipStream_t s, Args... args)
+inline void launch2d(void (*kernel)(KArgs...), unsigned grid_x, unsigned grid_y, hipStream_t s, Args... args)
 {
     hipEvent_t e0 = t_start_event, e1 = t_stop_event;
     t_start_event = nullptr;
     t_stop_event = nullptr;
-    hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, s, e0, e1, 0, static_cast<KArgs>(args)...);
+    hipExtLaunchKernelGGL(kernel, dim3(grid_x, grid_y), dim3(kThreads), 0, s, e0, e1, 0, static_cast<KArgs>(args)...);
+}
+
+template <typename... KArgs, typename... Args>
+inline void launch(void (*kernel)(KArgs...), unsigned grid, hipStream_t s, Args... args)
+{
+    launch2d(kernel, grid, 1u, s, args...);
 }
 
 template <int B>
@@ -88,29 +94,79 @@ void launch_dequantize(const int8_t *codes, const float *scales, int64_t n, uint
 }
 
 // Single-launch chain, measured on MI355X (27B-shaped size): 4 tiles per thread and one partial of look-ahead
-// is fastest (62.7 us); deeper look-ahead (2..8 partials in flight) is 5-12 % slower, 1024-thread groups too.
+// is fastest (62.7 us); deeper look-ahead (2..8 partials in flight) was 5-12 % slower, 1024-thread groups too.
 #ifndef EQUARX_TILES_CHAIN
 #define EQUARX_TILES_CHAIN 4
 #endif
-#ifndef EQUARX_CHAIN_DEPTH
-#define EQUARX_CHAIN_DEPTH 1       // partials a thread keeps in flight in the single-launch chain
-#endif
 constexpr int kTilesChain = EQUARX_TILES_CHAIN;
-constexpr int kChainDepth = EQUARX_CHAIN_DEPTH;
 static_assert(kMaxPartials == EQUARX_MAX_PARTIALS, "header and device limit differ");
 
-template <int B>
-void launch_chain(const PartialTable &tab, int P, int64_t n, uint16_t *out, int8_t *wire_codes, float *wire_scales,
-                  int64_t c_step, int64_t s_step, hipStream_t s)
+// Shape of a chain launch: the whole tensor in array order, or (ring layout) one grid row per shard.
+struct ChainGrid {
+    unsigned x, y;
+    int64_t shard_elems;
+};
+
+inline ChainGrid chain_grid(int64_t n, int32_t block, int32_t P, bool ring)
 {
-    const unsigned grid = grid_for(n, kTilesChain);
-    if (wire_codes) {
-        launch(chain_kernel<B, kTilesChain, kChainDepth, true>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step,
-               blocks_of(n, B));
+    ChainGrid g;
+    if (ring) {
+        const int64_t nb = blocks_of(n, block);
+        g.shard_elems = (nb + P - 1) / P * block;           // ceil(nb / P) blocks per shard
+        g.x = grid_for(g.shard_elems, kTilesChain);
+        g.y = (unsigned)P;
     } else {
-        launch(chain_kernel<B, kTilesChain, kChainDepth, false>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step,
-               blocks_of(n, B));
+        g.shard_elems = 0;
+        g.x = grid_for(n, kTilesChain);
+        g.y = 1;
     }
+    return g;
+}
+
+template <int B>
+void launch_chain(const PartialTable &tab, int P, int64_t n, bool rs, bool ag, bool ring, uint16_t *out,
+                  int8_t *wire_codes, float *wire_scales, int64_t c_step, int64_t s_step, hipStream_t s)
+{
+    const ChainGrid g = chain_grid(n, B, P, ring);
+#define EQUARX_CHAIN(RS, AG, WIRE)                                                                                  \
+    launch2d(chain_kernel<B, kTilesChain, RS, AG, WIRE>, g.x, g.y, s, tab, P, n, g.shard_elems, out, wire_codes,   \
+             wire_scales, c_step, s_step)
+    if (rs && ag) {
+        if (wire_codes) {
+            EQUARX_CHAIN(true, true, true);
+        } else {
+            EQUARX_CHAIN(true, true, false);
+        }
+    } else if (rs) {
+        EQUARX_CHAIN(true, false, false);
+    } else {
+        EQUARX_CHAIN(false, true, false);
+    }
+#undef EQUARX_CHAIN
+}
+
+template <int B>
+void launch_semi(const PartialTable &tab, int P, int64_t n, bool ag, bool ring, uint16_t *out, hipStream_t s)
+{
+    const ChainGrid g = chain_grid(n, B, P, ring);
+    if (ag) {
+        launch2d(semi_kernel<B, kTilesChain, true>, g.x, g.y, s, tab, P, n, g.shard_elems, out);
+    } else {
+        launch2d(semi_kernel<B, kTilesChain, false>, g.x, g.y, s, tab, P, n, g.shard_elems, out);
+    }
+}
+
+// Validates the P device pointers of a chain call and copies them into the kernel's table.
+inline int fill_table(const void *const *partials_bf16, int32_t P, const void *out_bf16, PartialTable &tab)
+{
+    for (int32_t i = 0; i < kMaxPartials; ++i) tab.x[i] = nullptr;
+    for (int32_t i = 0; i < P; ++i) {
+        if (!partials_bf16[i]) return EQUARX_NULL_POINTER;
+        if (misaligned(partials_bf16[i], kAlign)) return EQUARX_MISALIGNED;
+        if (partials_bf16[i] == out_bf16) return EQUARX_BAD_SHAPE;
+        tab.x[i] = static_cast<const uint16_t *>(partials_bf16[i]);
+    }
+    return EQUARX_OK;
 }
 
 #define EQUARX_DISPATCH_BLOCK(block, CALL)      \
@@ -298,19 +354,46 @@ int equarx_reduce_fused(const void *const *partials_bf16, int32_t P, int64_t n, 
     if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
     if (wire_codes && (misaligned(wire_codes, kAlign) || misaligned(wire_scales, kAlign))) return EQUARX_MISALIGNED;
     PartialTable tab;
-    for (int32_t i = 0; i < kMaxPartials; ++i) tab.x[i] = nullptr;
-    for (int32_t i = 0; i < P; ++i) {
-        if (!partials_bf16[i]) return EQUARX_NULL_POINTER;
-        if (misaligned(partials_bf16[i], kAlign)) return EQUARX_MISALIGNED;
-        if (partials_bf16[i] == out_bf16) return EQUARX_BAD_SHAPE;
-        tab.x[i] = static_cast<const uint16_t *>(partials_bf16[i]);
-    }
+    if (int st = fill_table(partials_bf16, P, out_bf16, tab)) return st;
     const int64_t c_step = equarx_wire_row_codes(n);
     const int64_t s_step = equarx_wire_row_scales(n, block);
     hipStream_t hs = static_cast<hipStream_t>(stream);
-#define CALL(BB) launch_chain<BB>(tab, P, n, static_cast<uint16_t *>(out_bf16), wire_codes, wire_scales, c_step, s_step, hs)
+#define CALL(BB)                                                                                               \
+    launch_chain<BB>(tab, P, n, true, true, false, static_cast<uint16_t *>(out_bf16), wire_codes, wire_scales, \
+                     c_step, s_step, hs)
     EQUARX_DISPATCH_BLOCK(block, CALL)
 #undef CALL
+    return launch_status();
+}
+
+int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block, uint32_t flags,
+                          void *out_bf16, void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    const uint32_t known = EQUARX_SEMI_LOOP | EQUARX_RS_UNQUANTIZED | EQUARX_AG_UNQUANTIZED | EQUARX_RING_ORDER;
+    if (flags & ~known) return EQUARX_BAD_SHAPE;
+    const bool semi = flags & EQUARX_SEMI_LOOP, rs = !(flags & EQUARX_RS_UNQUANTIZED);
+    const bool ag = !(flags & EQUARX_AG_UNQUANTIZED), ring = flags & EQUARX_RING_ORDER;
+    if (!rs && !ag) return EQUARX_BAD_SHAPE;        // nothing quantized: not this library's business
+    if (semi && !rs) return EQUARX_BAD_SHAPE;       // the semi-loop is a reduce-scatter schedule
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
+    PartialTable tab;
+    if (int st = fill_table(partials_bf16, P, out_bf16, tab)) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    uint16_t *out = static_cast<uint16_t *>(out_bf16);
+    if (semi) {
+#define CALL(BB) launch_semi<BB>(tab, P, n, ag, ring, out, hs)
+        EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+    } else {
+#define CALL(BB) launch_chain<BB>(tab, P, n, rs, ag, ring, out, nullptr, nullptr, 0, 0, hs)
+        EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+    }
     return launch_status();
 }
 

@@ -246,7 +246,13 @@ __device__ __forceinline__ void block_quotients_ieee(float a, float &scale, floa
 // Quantize the 8 values a lane holds, given that the G lanes of its group hold
 // one block.  r[i] receives the code of t[i] as a float (an integer in
 // [-127, 127]); `scale` is the block's scale (the same in every lane of the group).
-template <int G>
+//
+// kPositiveZero: a code that rounds to zero from below is -0.0 as a float,
+// where the int8 code converted back would be +0.0.  Kernels that keep the
+// codes as floats and multiply them again set this flag, which adds +0.0
+// (turning -0.0 into +0.0 and changing nothing else); the sign of a zero
+// product would otherwise leak into a sum whose other term is -0.0.
+template <int G, bool kPositiveZero = false>
 __device__ __forceinline__ void quantize_lane_f(const float (&t)[8], float (&r)[8], float &scale)
 {
     float m = 0.0f;
@@ -260,6 +266,7 @@ __device__ __forceinline__ void quantize_lane_f(const float (&t)[8], float (&r)[
     for (int i = 0; i < 8; ++i) {
         // |t*inv| <= 127*(1+2^-23): rounds to at most 127, no clamp needed
         r[i] = __builtin_rintf(t[i] * inv);
+        if (kPositiveZero) r[i] += 0.0f;
     }
 }
 
@@ -420,11 +427,20 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const int8_t *__re
 }
 
 // ---------------------------------------------------------------- the whole chain in one launch
-// Blocks never interact, so a workgroup can run all P-1 hops on its own tiles
-// with the running codes and scale held in registers: the same operations in
-// the same order as the hop-by-hop passes, hence the same bits.  The partials
-// are read once each; the wire is written only if the caller keeps it (kWire)
-// and is never read back.
+// Blocks never interact, so a workgroup can run all hops on its own tiles with
+// the running sum held in registers: the same operations in the same order as
+// the hop-by-hop passes, hence the same bits.  The partials are read once each
+// (the next one's loads are issued before the current hop's arithmetic); the
+// wire is written only if the caller keeps it (kWire) and is never read back.
+//
+// Template knobs (the stage selection of Sec. 3.4):
+//   kRS  what a device forwards during the reduce-scatter is quantized
+//        (otherwise the running sum stays fp32 and is added with plain adds);
+//   kAG  the finished sum is quantized once more for the all-gather and
+//        dequantized (otherwise it is narrowed to bf16 directly).
+// Ring layout: with shard_elems > 0 the tensor is cut into gridDim.y shards of
+// shard_elems elements (a multiple of B) and shard k is reduced in the rotated
+// order rot+0, rot+1, ... (mod P) with rot = k + rot_bias.
 
 constexpr int kMaxPartials = 64;
 
@@ -432,111 +448,239 @@ struct PartialTable {
     const uint16_t *x[kMaxPartials];
 };
 
-// D = how many partials' tiles a thread keeps in flight: the loads of partial
-// i+D are issued when partial i is consumed, so that memory latency (a few
-// thousand cycles under load) is covered by D hops of arithmetic.
-template <int B, int K, int D, bool kWire, bool kFull>
-__device__ __forceinline__ void chain_body(const PartialTable &tab, int P, int64_t n, uint16_t *__restrict__ out,
-                                           int8_t *__restrict__ wire_codes, float *__restrict__ wire_scales,
-                                           int64_t c_step, int64_t s_step, int64_t nb, int64_t wg_at)
+template <int K, bool kFull>
+__device__ __forceinline__ void load_tiles(const uint16_t *p, int64_t wg_at, int64_t n, u32x4 (&v)[K])
+{
+    const int lane_at = threadIdx.x * kLaneElems;
+#pragma unroll
+    for (int k = 0; k < K; ++k) v[k] = load_bf16x8(p, wg_at + k * kTileElems + lane_at, n, kFull);
+}
+
+// Writes what the wire carries after a quantization of one tile (8 codes per
+// lane starting at element `at`): row `row` of the kept wire.
+template <int B, bool kFull>
+__device__ __forceinline__ void store_wire_tile(int8_t *__restrict__ wire_codes, float *__restrict__ wire_scales,
+                                                int64_t c_step, int64_t s_step, int row, int64_t at, int64_t n,
+                                                const float (&r)[8], float s)
 {
     constexpr int G = B / kLaneElems;
-    const int lane_at = threadIdx.x * kLaneElems;
-    const bool writes_scale = (threadIdx.x % G) == 0;
+    store_i8x8(wire_codes + (int64_t)row * c_step, at, n, kFull, pack_codes(r));
+    if ((threadIdx.x % G) == 0 && (kFull || at < n)) wire_scales[(int64_t)row * s_step + at / B] = s;
+}
 
-    float r[K][8];      // running codes, as floats
-    float s[K];         // running scales
-    u32x4 buf[D][K];    // ring of loaded tiles: partial i sits in slot i % D
+// out = bf16(v) for the 8 fp32 values of one lane.
+template <bool kFull>
+__device__ __forceinline__ void store_narrowed_tile(uint16_t *__restrict__ out, int64_t at, int64_t n,
+                                                    const float (&v)[8])
+{
+    u32x4 w;
+    w.x = narrow_bf16x2(v[0], v[1]);
+    w.y = narrow_bf16x2(v[2], v[3]);
+    w.z = narrow_bf16x2(v[4], v[5]);
+    w.w = narrow_bf16x2(v[6], v[7]);
+    store_bf16x8(out, at, n, kFull, w);
+}
 
-#pragma unroll
-    for (int d = 0; d < D; ++d) {
-        if (d < P) {
-#pragma unroll
-            for (int k = 0; k < K; ++k) buf[d][k] = load_bf16x8(tab.x[d], wg_at + k * kTileElems + lane_at, n, kFull);
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        float t[8];
-        widen_bf16x8(buf[0][k], t);
-        quantize_lane_f<G>(t, r[k], s[k]);
-    }
-    if (D < P) {
-#pragma unroll
-        for (int k = 0; k < K; ++k) buf[0][k] = load_bf16x8(tab.x[D], wg_at + k * kTileElems + lane_at, n, kFull);
-    }
-
-    for (int base = 1; base < P; base += D) {
-#pragma unroll
-        for (int d = 0; d < D; ++d) {
-            const int i = base + d;             // i % D == (1 + d) % D: the slot is a compile-time constant
-            constexpr int kSlotBias = 1;
-            const int slot = (kSlotBias + d) % D;
-            if (i < P) {
-                if (kWire) {
-#pragma unroll
-                    for (int k = 0; k < K; ++k) {
-                        const int64_t at = wg_at + k * kTileElems + lane_at;
-                        store_i8x8(wire_codes + (i - 1) * c_step, at, n, kFull, pack_codes(r[k]));
-                        const int64_t blk = at / B;
-                        if (writes_scale && (kFull || blk < nb)) wire_scales[(i - 1) * s_step + blk] = s[k];
-                    }
-                }
-                u32x4 xc[K];
-#pragma unroll
-                for (int k = 0; k < K; ++k) xc[k] = buf[slot][k];
-                if (i + D < P) {
-#pragma unroll
-                    for (int k = 0; k < K; ++k) {
-                        buf[slot][k] = load_bf16x8(tab.x[i + D], wg_at + k * kTileElems + lane_at, n, kFull);
-                    }
-                }
-#pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    float xf[8], t[8];
-                    widen_bf16x8(xc[k], xf);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(r[k][j], s[k], xf[j]);
-                    quantize_lane_f<G>(t, r[k], s[k]);
-                }
-            }
-        }
-    }
-
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const int64_t at = wg_at + k * kTileElems + lane_at;
-        if (kWire) {
-            store_i8x8(wire_codes + (int64_t)(P - 1) * c_step, at, n, kFull, pack_codes(r[k]));
-            const int64_t blk = at / B;
-            if (writes_scale && (kFull || blk < nb)) wire_scales[(int64_t)(P - 1) * s_step + blk] = s[k];
-        }
-        // A float-valued code can be -0.0 where the int8 code is plain 0; adding +0.0 turns it into the
-        // +0.0 an int8 -> float conversion gives (the sign of a zero is the only place the two could differ:
-        // |t|, the scales and the integer codes do not see it).
+// The last step of a chain for one tile: quantize the finished fp32 sum once
+// more and dequantize it (quantized all-gather, Sec. 3.4), or narrow it directly.
+template <int B, bool kAG, bool kWire, bool kFull>
+__device__ __forceinline__ void finish_tile(const float (&t)[8], uint16_t *__restrict__ out,
+                                            int8_t *__restrict__ wire_codes, float *__restrict__ wire_scales,
+                                            int64_t c_step, int64_t s_step, int row, int64_t at, int64_t n)
+{
+    constexpr int G = B / kLaneElems;
+    if (kAG) {
+        float r[8], s;
+        quantize_lane_f<G, true>(t, r, s);      // +0.0 codes: the product below shows the sign of a zero
+        if (kWire) store_wire_tile<B, kFull>(wire_codes, wire_scales, c_step, s_step, row, at, n, r, s);
         float d[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) d[j] = (r[k][j] + 0.0f) * s[k];
-        u32x4 w;
-        w.x = narrow_bf16x2(d[0], d[1]);
-        w.y = narrow_bf16x2(d[2], d[3]);
-        w.z = narrow_bf16x2(d[4], d[5]);
-        w.w = narrow_bf16x2(d[6], d[7]);
-        store_bf16x8(out, at, n, kFull, w);
+        for (int j = 0; j < 8; ++j) d[j] = r[j] * s;
+        store_narrowed_tile<kFull>(out, at, n, d);
+    } else {
+        store_narrowed_tile<kFull>(out, at, n, t);
     }
 }
 
-template <int B, int K, int D, bool kWire>
-__global__ __launch_bounds__(kThreads) void chain_kernel(const PartialTable tab, int P, int64_t n,
+// Position -> partial index on a ring of P devices, without a division: the
+// callers only ever step by one.
+__device__ __forceinline__ int ring_next(int j, int P) { return j + 1 == P ? 0 : j + 1; }
+__device__ __forceinline__ int ring_prev(int j, int P) { return j == 0 ? P - 1 : j - 1; }
+
+// One hop on the K tiles of a workgroup: (what the previous device sends) = Q_B(t),
+// t = fma(codes, scale, x) -- or a plain fp32 add when the reduce-scatter is
+// not quantized.  The quantization does not need x, so it runs while x arrives.
+//
+// kPositiveZero (see quantize_lane_f) is needed only where the sign of a zero
+// sum can reach the output, i.e. when the all-gather is NOT quantized; with a
+// quantized all-gather a -0.0 code can only flip the sign of zero sums along
+// the chain, which no max-abs, scale or integer code sees, and the last
+// quantization hands out +0.0 codes.
+template <int B, int K, bool kRS, bool kWire, bool kPositiveZero, bool kFull>
+__device__ __forceinline__ void hop_tiles(float (&t)[K][8], const u32x4 (&x)[K], int8_t *__restrict__ wire_codes,
+                                          float *__restrict__ wire_scales, int64_t c_step, int64_t s_step, int row,
+                                          int64_t wg_at, int64_t n)
+{
+    constexpr int G = B / kLaneElems;
+    const int lane_at = threadIdx.x * kLaneElems;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        if (kRS) {
+            float r[8], s;
+            quantize_lane_f<G, kPositiveZero>(t[k], r, s);
+            if (kWire) {
+                store_wire_tile<B, kFull>(wire_codes, wire_scales, c_step, s_step, row,
+                                          wg_at + k * kTileElems + lane_at, n, r, s);
+            }
+            float xf[8];
+            widen_bf16x8(x[k], xf);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[k][j] = __builtin_fmaf(r[j], s, xf[j]);
+        } else {
+            float xf[8];
+            widen_bf16x8(x[k], xf);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[k][j] = t[k][j] + xf[j];
+        }
+    }
+}
+
+// Full-loop adder chain over the partials in the order rot, rot+1, ... (mod P).
+// Per tile the only state carried from hop to hop is the fp32 sum t.  Each hop
+// loads its partial and then computes; the quantization of the running sum
+// does not need the new data and runs while it arrives.  Starting the loads a
+// hop (or several) ahead was measured and is SLOWER on MI355X (63 -> 67..72 us
+// at the 27B-shaped size): with three waves per SIMD and four 16-byte loads
+// per lane in flight the memory system is already saturated, and more
+// outstanding requests only lengthen its queues.
+template <int B, int K, bool kRS, bool kAG, bool kWire, bool kFull>
+__device__ __forceinline__ void chain_body(const PartialTable &tab, int P, int rot, int64_t n,
+                                           uint16_t *__restrict__ out, int8_t *__restrict__ wire_codes,
+                                           float *__restrict__ wire_scales, int64_t c_step, int64_t s_step,
+                                           int64_t wg_at)
+{
+    const int lane_at = threadIdx.x * kLaneElems;
+    float t[K][8];      // running fp32 sum
+    u32x4 x0[K], xv[K];     // separate registers: partial 1 may be requested before partial 0 has arrived
+
+    int j = rot >= P ? rot - P : rot;               // rot < 2P
+    load_tiles<K, kFull>(tab.x[j], wg_at, n, x0);
+#pragma unroll
+    for (int k = 0; k < K; ++k) widen_bf16x8(x0[k], t[k]);
+    for (int i = 1; i < P; ++i) {
+        j = ring_next(j, P);
+        load_tiles<K, kFull>(tab.x[j], wg_at, n, xv);
+        hop_tiles<B, K, kRS, kWire, !kAG, kFull>(t, xv, wire_codes, wire_scales, c_step, s_step, i - 1, wg_at, n);
+    }
+
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        finish_tile<B, kAG, kWire, kFull>(t[k], out, wire_codes, wire_scales, c_step, s_step, P - 1,
+                                          wg_at + k * kTileElems + lane_at, n);
+    }
+}
+
+// Where a workgroup works: its shard [lo, hi) and rotation, its first element.
+struct Span {
+    int64_t wg_at, hi;
+    int rot;
+    bool any;
+};
+
+template <int K>
+__device__ __forceinline__ Span workgroup_span(int64_t n, int64_t shard_elems, int rot_bias)
+{
+    Span sp;
+    int64_t lo = 0;
+    sp.hi = n;
+    sp.rot = 0;
+    if (shard_elems > 0) {
+        lo = (int64_t)blockIdx.y * shard_elems;
+        sp.hi = lo + shard_elems < n ? lo + shard_elems : n;
+        sp.rot = (int)blockIdx.y + rot_bias;
+    }
+    sp.wg_at = lo + (int64_t)blockIdx.x * (kTileElems * K);
+    sp.any = sp.wg_at < sp.hi;
+    return sp;
+}
+
+template <int B, int K, bool kRS, bool kAG, bool kWire>
+__global__ __launch_bounds__(kThreads) void chain_kernel(const PartialTable tab, int P, int64_t n, int64_t shard_elems,
                                                          uint16_t *__restrict__ out, int8_t *__restrict__ wire_codes,
                                                          float *__restrict__ wire_scales, int64_t c_step,
-                                                         int64_t s_step, int64_t nb)
+                                                         int64_t s_step)
 {
-    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
-    if (wg_at + kTileElems * K <= n) {
-        chain_body<B, K, D, kWire, true>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, nb, wg_at);
+    const Span sp = workgroup_span<K>(n, shard_elems, 1);     // shard k: devices k+1, k+2, ..., k
+    if (!sp.any) return;                                      // uniform over the workgroup
+    if (sp.wg_at + kTileElems * K <= sp.hi) {
+        chain_body<B, K, kRS, kAG, kWire, true>(tab, P, sp.rot, sp.hi, out, wire_codes, wire_scales, c_step, s_step,
+                                                sp.wg_at);
     } else {
-        chain_body<B, K, D, kWire, false>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, nb, wg_at);
+        chain_body<B, K, kRS, kAG, kWire, false>(tab, P, sp.rot, sp.hi, out, wire_codes, wire_scales, c_step, s_step,
+                                                 sp.wg_at);
+    }
+}
+
+// Semi-loop adder tree (Sec. 3.3).  Position 0 (device rot) owns the shard; the
+// other positions follow in ring order.  With h = P/2 the counter-clockwise
+// chain h+1, h+2, ..., P-1 and the clockwise chain h, h-1, ..., 1 each end in a
+// quantized send to the owner, which adds them to its own fp32 shard, the
+// shorter counter-clockwise chain first.
+template <int B, int K, bool kAG, bool kFull>
+__device__ __forceinline__ void semi_body(const PartialTable &tab, int P, int rot, int64_t n,
+                                          uint16_t *__restrict__ out, int64_t wg_at)
+{
+    const int lane_at = threadIdx.x * kLaneElems;
+    const int h = P / 2;
+    float own[K][8], t[K][8];
+    u32x4 xv[K];
+
+    const int owner = rot >= P ? rot - P : rot;     // rot < 2P
+    load_tiles<K, kFull>(tab.x[owner], wg_at, n, xv);
+#pragma unroll
+    for (int k = 0; k < K; ++k) widen_bf16x8(xv[k], own[k]);
+
+#pragma unroll 1
+    for (int dir = 0; dir < 2; ++dir) {
+        // dir 0: positions h+1 .. P-1 ascending; dir 1: positions h .. 1 descending
+        const int count = dir == 0 ? P - 1 - h : h;
+        if (count <= 0) continue;
+        int j = owner + (dir == 0 ? h + 1 : h);     // < 2P
+        if (j >= P) j -= P;
+        load_tiles<K, kFull>(tab.x[j], wg_at, n, xv);
+#pragma unroll
+        for (int k = 0; k < K; ++k) widen_bf16x8(xv[k], t[k]);
+        for (int c = 1; c < count; ++c) {
+            j = dir == 0 ? ring_next(j, P) : ring_prev(j, P);
+            load_tiles<K, kFull>(tab.x[j], wg_at, n, xv);
+            hop_tiles<B, K, true, false, !kAG, kFull>(t, xv, nullptr, nullptr, 0, 0, 0, wg_at, n);
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            constexpr int G = B / kLaneElems;
+            float r[8], s;
+            quantize_lane_f<G, !kAG>(t[k], r, s);                      // the send that reaches the owner
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) own[k][jj] = __builtin_fmaf(r[jj], s, own[k][jj]);
+        }
+    }
+
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        finish_tile<B, kAG, false, kFull>(own[k], out, nullptr, nullptr, 0, 0, 0, wg_at + k * kTileElems + lane_at, n);
+    }
+}
+
+template <int B, int K, bool kAG>
+__global__ __launch_bounds__(kThreads) void semi_kernel(const PartialTable tab, int P, int64_t n, int64_t shard_elems,
+                                                        uint16_t *__restrict__ out)
+{
+    const Span sp = workgroup_span<K>(n, shard_elems, 0);     // shard k: owner is device k
+    if (!sp.any) return;
+    if (sp.wg_at + kTileElems * K <= sp.hi) {
+        semi_body<B, K, kAG, true>(tab, P, sp.rot, sp.hi, out, sp.wg_at);
+    } else {
+        semi_body<B, K, kAG, false>(tab, P, sp.rot, sp.hi, out, sp.wg_at);
     }
 }
 

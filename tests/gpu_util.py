@@ -87,3 +87,11 @@ def gpu_chain_fused(partials_u16, B, keep_wire=True):
     eq.equarx_reduce_fused(parts, B, out)
     torch.cuda.synchronize()
     return host_u16(out)
+
+
+def gpu_variant(partials_u16, B, flags):
+    parts = [dev_bf16(p) for p in partials_u16]
+    out = torch.full((parts[0].numel(),), 7.0, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_variant(parts, B, flags, out)
+    torch.cuda.synchronize()
+    return host_u16(out)

@@ -120,6 +120,18 @@ def test_validation_rejects_before_launch(lib):
     assert rf(ok4, 4, n, 7, OUT, None, None, None) == B.STATUS_BAD_BLOCK
     assert rf(ok4, 4, -3, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE
     assert rf(ok4, 4, 0, blk, None, None, None, None) == B.STATUS_OK
+    rv = lib.equarx_reduce_variant
+    assert rv(ok4, 4, n, blk, 2 | 4, OUT, None) == B.STATUS_BAD_SHAPE
+    assert rv(ok4, 4, n, blk, 1 | 2, OUT, None) == B.STATUS_BAD_SHAPE
+    assert rv(ok4, 4, n, blk, 16, OUT, None) == B.STATUS_BAD_SHAPE
+    assert rv(ok4, 0, n, blk, 0, OUT, None) == B.STATUS_BAD_SHAPE
+    assert rv(None, 4, n, blk, 1, OUT, None) == B.STATUS_NULL_POINTER
+    assert rv(ok4, 4, n, blk, 8, None, None) == B.STATUS_NULL_POINTER
+    assert rv(ok4, 4, n, blk, 1, OUT + 4, None) == B.STATUS_MISALIGNED
+    assert rv(table(A, A, A, ODD), 4, n, blk, 4, OUT, None) == B.STATUS_MISALIGNED
+    assert rv(table(A, OUT, A, A), 4, n, blk, 9, OUT, None) == B.STATUS_BAD_SHAPE
+    assert rv(ok4, 4, n, 96, 0, OUT, None) == B.STATUS_BAD_BLOCK
+    assert rv(ok4, 4, 0, blk, 1, None, None) == B.STATUS_OK
     # calibration copy
     cp = lib.equarx_calib_copy
     assert cp(A, A + 0x1000, 0, None) == B.STATUS_OK

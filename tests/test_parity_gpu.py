@@ -347,3 +347,73 @@ def test_block_quotients_equal_host_division(gpu):
     eq.equarx_eval_quotients(tiny, s2, v2)
     torch.cuda.synchronize()
     assert s2.tolist() == [0, 0, 0, 0] and v2.tolist() == [0, 0, 0, 0]
+
+
+# ----------------------------------------------------------------------------- variants of the chain
+
+def _oracle_variant(oracle, parts, B, flags):
+    semi, rs = bool(flags & eq.SEMI_LOOP), not (flags & eq.RS_UNQUANTIZED)
+    ag, ring = not (flags & eq.AG_UNQUANTIZED), bool(flags & eq.RING_ORDER)
+    if ring:
+        return oracle.reduce_ring(parts, B, semi=semi, quantize_rs=rs, quantize_ag=ag)
+    if semi:
+        return oracle.reduce_semi_loop(parts, B, ag)
+    return oracle.reduce_stages(parts, B, rs, ag)
+
+
+VARIANT_FLAGS = {
+    "full": 0,
+    "rs_only": eq.AG_UNQUANTIZED,
+    "ag_only": eq.RS_UNQUANTIZED,
+    "semi": eq.SEMI_LOOP,
+    "semi_rs_only": eq.SEMI_LOOP | eq.AG_UNQUANTIZED,
+    "ring": eq.RING_ORDER,
+    "ring_rs_only": eq.RING_ORDER | eq.AG_UNQUANTIZED,
+    "ring_ag_only": eq.RING_ORDER | eq.RS_UNQUANTIZED,
+    "ring_semi": eq.RING_ORDER | eq.SEMI_LOOP,
+    "ring_semi_rs_only": eq.RING_ORDER | eq.SEMI_LOOP | eq.AG_UNQUANTIZED,
+}
+
+
+@pytest.mark.parametrize("name", sorted(VARIANT_FLAGS))
+def test_variant_parity(gpu, oracle, name):
+    flags = VARIANT_FLAGS[name]
+    cases = [(4, 4096, 256, "normal"), (8, 2048 * 9 + 1024 + 40, 64, "lognormal"), (1, 3000, 32, "normal"),
+             (2, 8192 * 2 + 7, 128, "student"), (3, 5000, 512, "normal"), (7, 8192 * 3 + 2048 + 8, 32, "tiny"),
+             (16, 64 * 5376 // 4, 128, "normal"), (5, 300, 256, "sparse"), (64, 2048 + 100, 64, "normal")]
+    for P, n, B, kind in cases:
+        parts = [gpu.bf16_of(_values(kind, n, 900 + 7 * p + P)) for p in range(P)]
+        got = gpu.gpu_variant(parts, B, flags)
+        want = _oracle_variant(oracle, parts, B, flags)
+        assert (got == want).all(), (name, P, n, B, kind, int((got != want).sum()))
+
+
+def test_variant_workloads(gpu, oracle):
+    for case in ("c2_rows24", "c3_rows24", "c4"):
+        w = CHAIN_CASES[case]
+        parts = [wl.as_u16(p) for p in wl.make_partials(w)]
+        for name, flags in VARIANT_FLAGS.items():
+            assert (gpu.gpu_variant(parts, w.block, flags) == _oracle_variant(oracle, parts, w.block, flags)).all(), (case, name)
+
+
+def test_variant_bad_flags(gpu):
+    x = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
+    out = torch.empty_like(x)
+    for flags in (eq.RS_UNQUANTIZED | eq.AG_UNQUANTIZED, eq.SEMI_LOOP | eq.RS_UNQUANTIZED, 16, 1 << 31):
+        with pytest.raises(eq.EquarxError) as e:
+            eq.equarx_reduce_variant([x, x], 256, flags, out)
+        assert e.value.status == eq.STATUS_BAD_SHAPE
+
+
+def test_variant_error_ordering_as_in_the_paper(gpu, oracle):
+    """Sec. 4.1 / Fig. 7 on the GPU path: AG-only < semi-loop < full-loop in MSE (8 devices, block 64, N(0,1))."""
+    P, n, B = 8, 1 << 20, 64
+    parts = [gpu.bf16_of(_values("normal", n, 4242 + p)) for p in range(P)]
+    ref = sum(oracle.bf16_to_f32(p).astype(np.float64) for p in parts)
+
+    def mse(flags):
+        return float(np.mean((oracle.bf16_to_f32(gpu.gpu_variant(parts, B, flags)).astype(np.float64) - ref) ** 2))
+
+    full, semi, ag_only = mse(0), mse(eq.SEMI_LOOP), mse(eq.RS_UNQUANTIZED)
+    assert ag_only < semi < full
+    assert 0.0014 / 1.5 < full < 0.0014 * 1.5 and 0.001 / 1.5 < semi < 0.001 * 1.5 and 0.0003 / 1.5 < ag_only < 0.0003 * 1.5
