@@ -168,6 +168,32 @@ int equarx_reduce_fused(const void *const *partials_bf16, int32_t P, int64_t n, 
 int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block, uint32_t flags,
                           void *out_bf16, void *stream);
 
+/*
+ * Flat one-shot reduce: the reduce-scatter done as an all-to-all followed by
+ * a local reduction (the decomposition Sec. 2 describes for ZeRO++; on a full
+ * xGMI mesh, where a ring is bound by one link of seven, it is the natural
+ * shape).  Every other device has quantized its shard ONCE with
+ * equarx_quantize; the owner holds its own bf16 shard and the R received
+ * (codes, scales) pairs and computes
+ *
+ *   acc = fp32(local);  acc = fma(fp32(codes[r]), scales[r][block], acc)  r = 0 .. R-1, in array order
+ *   (codes_out, scales_out) = quantize(acc)         what the all-gather carries (Sec. 3.4)
+ *   out = bf16(fp32(codes_out) * scales_out[block])
+ *
+ * Two quantizations per value instead of the ring's P.
+ *
+ *   local_bf16 [n]     device.
+ *   codes, scales      HOST arrays of R device pointers (int8 [n] / fp32 [nb]
+ *                      each); 0 <= R < EQUARX_MAX_PARTIALS; read before return.
+ *   out_bf16 [n]       device or NULL.
+ *   codes_out [n], scales_out [nb]   device or both NULL; at least one of
+ *                      out_bf16 and the (codes_out, scales_out) pair must be given.
+ * Outputs must not alias inputs.
+ */
+int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const float *const *scales, int32_t R,
+                       int64_t n, int32_t block, void *out_bf16, int8_t *codes_out, float *scales_out,
+                       void *stream);
+
 /* Bytes of workspace equarx_reduce_quantized needs (0 for invalid arguments). */
 size_t equarx_workspace_bytes(int32_t P, int64_t n, int32_t block);
 

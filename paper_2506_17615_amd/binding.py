@@ -36,6 +36,8 @@ SIGNATURES = {
     "equarx_reduce_quantized": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp, _vp, _vp]),
     "equarx_reduce_fused": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp, _vp]),
     "equarx_reduce_variant": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp]),
+    "equarx_reduce_flat": (ctypes.c_int, [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp,
+                                          _vp]),
     "equarx_workspace_bytes": (_sz, [_i32, _i64, _i32]),
     "equarx_num_blocks": (_i64, [_i64, _i32]),
     "equarx_wire_row_codes": (_i64, [_i64]),
@@ -198,6 +200,29 @@ def equarx_reduce_variant(partials, block: int, flags: int, out_bf16) -> None:
     _need(out_bf16, torch.bfloat16, n, "out_bf16")
     table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
     _check(load().equarx_reduce_variant(table, P, n, block, flags, _ptr(out_bf16), _stream()), "equarx_reduce_variant")
+
+
+def equarx_reduce_flat(local_bf16, codes_list, scales_list, block: int, out_bf16=None, codes_out=None,
+                       scales_out=None) -> None:
+    """Flat one-shot reduce of a local bf16 shard and R received (codes, scales) pairs."""
+    n = local_bf16.numel()
+    nb = num_blocks(n, block)
+    R = len(codes_list)
+    if len(scales_list) != R:
+        raise ValueError("codes and scales lists differ in length")
+    _need(local_bf16, torch.bfloat16, n, "local_bf16")
+    for c, s in zip(codes_list, scales_list):
+        _need(c, torch.int8, n, "codes")
+        _need(s, torch.float32, nb, "scales")
+    if out_bf16 is not None:
+        _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    if codes_out is not None or scales_out is not None:
+        _need(codes_out, torch.int8, n, "codes_out")
+        _need(scales_out, torch.float32, nb, "scales_out")
+    ctab = (_vp * max(R, 1))(*[c.data_ptr() for c in codes_list])
+    stab = (_vp * max(R, 1))(*[s.data_ptr() for s in scales_list])
+    _check(load().equarx_reduce_flat(_ptr(local_bf16), ctab, stab, R, n, block, _ptr(out_bf16), _ptr(codes_out),
+                                     _ptr(scales_out), _stream()), "equarx_reduce_flat")
 
 
 def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:

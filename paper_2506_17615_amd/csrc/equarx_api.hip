@@ -156,6 +156,26 @@ void launch_semi(const PartialTable &tab, int P, int64_t n, bool ag, bool ring, 
     }
 }
 
+#ifndef EQUARX_TILES_FLAT
+#define EQUARX_TILES_FLAT 4
+#endif
+constexpr int kTilesFlat = EQUARX_TILES_FLAT;
+
+template <int B>
+void launch_flat(const uint16_t *local, const WireTable &tab, int R, int64_t n, uint16_t *out, int8_t *codes_out,
+                 float *scales_out, hipStream_t s)
+{
+    const unsigned grid = grid_for(n, kTilesFlat);
+    const int64_t nb = blocks_of(n, B);
+    if (out && codes_out) {
+        launch(flat_kernel<B, kTilesFlat, true, true>, grid, s, local, tab, R, n, out, codes_out, scales_out, nb);
+    } else if (out) {
+        launch(flat_kernel<B, kTilesFlat, true, false>, grid, s, local, tab, R, n, out, codes_out, scales_out, nb);
+    } else {
+        launch(flat_kernel<B, kTilesFlat, false, true>, grid, s, local, tab, R, n, out, codes_out, scales_out, nb);
+    }
+}
+
 // Validates the P device pointers of a chain call and copies them into the kernel's table.
 inline int fill_table(const void *const *partials_bf16, int32_t P, const void *out_bf16, PartialTable &tab)
 {
@@ -394,6 +414,40 @@ int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n
         EQUARX_DISPATCH_BLOCK(block, CALL)
 #undef CALL
     }
+    return launch_status();
+}
+
+int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const float *const *scales, int32_t R,
+                       int64_t n, int32_t block, void *out_bf16, int8_t *codes_out, float *scales_out, void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (R < 0 || R >= EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (R > 0 && (!codes || !scales)) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!local_bf16) return EQUARX_NULL_POINTER;
+    if ((codes_out == nullptr) != (scales_out == nullptr)) return EQUARX_NULL_POINTER;
+    if (!out_bf16 && !codes_out) return EQUARX_NULL_POINTER;                    // nothing to write
+    if (misaligned(local_bf16, kAlign) || (out_bf16 && misaligned(out_bf16, kAlign))) return EQUARX_MISALIGNED;
+    if (codes_out && (misaligned(codes_out, kAlign) || misaligned(scales_out, kAlign))) return EQUARX_MISALIGNED;
+    if (out_bf16 == local_bf16) return EQUARX_BAD_SHAPE;
+    WireTable tab;
+    for (int32_t r = 0; r < kMaxPartials; ++r) {
+        tab.codes[r] = nullptr;
+        tab.scales[r] = nullptr;
+    }
+    for (int32_t r = 0; r < R; ++r) {
+        if (!codes[r] || !scales[r]) return EQUARX_NULL_POINTER;
+        if (misaligned(codes[r], kAlign) || misaligned(scales[r], kAlign)) return EQUARX_MISALIGNED;
+        if (codes[r] == codes_out || scales[r] == scales_out) return EQUARX_BAD_SHAPE;
+        tab.codes[r] = codes[r];
+        tab.scales[r] = scales[r];
+    }
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+#define CALL(BB)                                                                                                  \
+    launch_flat<BB>(static_cast<const uint16_t *>(local_bf16), tab, R, n, static_cast<uint16_t *>(out_bf16), codes_out, \
+                    scales_out, hs)
+    EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
     return launch_status();
 }
 

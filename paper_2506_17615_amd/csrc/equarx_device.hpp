@@ -684,6 +684,85 @@ __global__ __launch_bounds__(kThreads) void semi_kernel(const PartialTable tab, 
     }
 }
 
+// ---------------------------------------------------------------- flat one-shot reduce
+// The reduce-scatter as an all-to-all followed by a local reduction (the
+// decomposition Sec. 2 describes for ZeRO++, and the shape a full xGMI mesh
+// favours over a ring): the owner of a shard holds its own bf16 shard and R
+// received (codes, scales) pairs, each quantized once by its sender.  It
+// dequantizes and accumulates them in fp32 in array order -- one fused
+// multiply-add each -- and quantizes the sum once for the all-gather.
+
+struct WireTable {
+    const int8_t *codes[kMaxPartials];
+    const float *scales[kMaxPartials];
+};
+
+template <int B, int K, bool kOutBf16, bool kOutWire, bool kFull>
+__device__ __forceinline__ void flat_body(const uint16_t *__restrict__ local, const WireTable &tab, int R, int64_t n,
+                                          uint16_t *__restrict__ out, int8_t *__restrict__ codes_out,
+                                          float *__restrict__ scales_out, int64_t nb, int64_t wg_at)
+{
+    constexpr int G = B / kLaneElems;
+    const int lane_at = threadIdx.x * kLaneElems;
+    float acc[K][8];
+    u32x4 xv[K];
+    load_tiles<K, kFull>(local, wg_at, n, xv);
+#pragma unroll
+    for (int k = 0; k < K; ++k) widen_bf16x8(xv[k], acc[k]);
+
+    for (int r = 0; r < R; ++r) {
+        const int8_t *c = tab.codes[r];
+        const float *sc = tab.scales[r];
+        u32x2 cv[K];
+        float sv[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int64_t at = wg_at + k * kTileElems + lane_at;
+            cv[k] = load_i8x8(c, at, n, kFull);
+            const int64_t blk = at / B;
+            sv[k] = (kFull || blk < nb) ? sc[blk] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            float qf[8];
+            widen_i8x8(cv[k], qf);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[k][j] = __builtin_fmaf(qf[j], sv[k], acc[k][j]);
+        }
+    }
+
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        float q[8], s;
+        quantize_lane_f<G, true>(acc[k], q, s);
+        if (kOutWire) {
+            store_i8x8(codes_out, at, n, kFull, pack_codes(q));
+            if ((threadIdx.x % G) == 0 && (kFull || at < n)) scales_out[at / B] = s;
+        }
+        if (kOutBf16) {
+            float d[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) d[j] = q[j] * s;
+            store_narrowed_tile<kFull>(out, at, n, d);
+        }
+    }
+}
+
+template <int B, int K, bool kOutBf16, bool kOutWire>
+__global__ __launch_bounds__(kThreads) void flat_kernel(const uint16_t *__restrict__ local, const WireTable tab, int R,
+                                                        int64_t n, uint16_t *__restrict__ out,
+                                                        int8_t *__restrict__ codes_out, float *__restrict__ scales_out,
+                                                        int64_t nb)
+{
+    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
+    if (wg_at + kTileElems * K <= n) {
+        flat_body<B, K, kOutBf16, kOutWire, true>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
+    } else {
+        flat_body<B, K, kOutBf16, kOutWire, false>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
+    }
+}
+
 // ---------------------------------------------------------------- self-tests of the arithmetic
 
 // Compares block_quotients with the IEEE division for the `count` consecutive

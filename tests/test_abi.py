@@ -132,6 +132,20 @@ def test_validation_rejects_before_launch(lib):
     assert rv(table(A, OUT, A, A), 4, n, blk, 9, OUT, None) == B.STATUS_BAD_SHAPE
     assert rv(ok4, 4, n, 96, 0, OUT, None) == B.STATUS_BAD_BLOCK
     assert rv(ok4, 4, 0, blk, 1, None, None) == B.STATUS_OK
+    fl = lib.equarx_reduce_flat
+    ctab, stab = table(A, A + 0x10000), table(A + 0x20000, A + 0x30000)
+    assert fl(A + 0x40000, ctab, stab, 2, n, blk, None, None, None, None) == B.STATUS_NULL_POINTER
+    assert fl(None, ctab, stab, 2, n, blk, OUT, None, None, None) == B.STATUS_NULL_POINTER
+    assert fl(A + 0x40000, None, stab, 2, n, blk, OUT, None, None, None) == B.STATUS_NULL_POINTER
+    assert fl(A + 0x40000, ctab, stab, 2, n, blk, OUT, A + 0x50000, None, None) == B.STATUS_NULL_POINTER
+    assert fl(A + 0x40000, ctab, stab, 64, n, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE
+    assert fl(A + 0x40000, ctab, stab, -1, n, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE
+    assert fl(A + 0x40000, table(A, ODD), stab, 2, n, blk, OUT, None, None, None) == B.STATUS_MISALIGNED
+    assert fl(A + 0x40000, table(A, 0), stab, 2, n, blk, OUT, None, None, None) == B.STATUS_NULL_POINTER
+    assert fl(A + 0x40000, ctab, stab, 2, n, blk, A + 0x40000, None, None, None) == B.STATUS_BAD_SHAPE
+    assert fl(A + 0x40000, ctab, stab, 2, n, blk, OUT + 8, None, None, None) == B.STATUS_MISALIGNED
+    assert fl(A + 0x40000, ctab, stab, 2, n, 33, OUT, None, None, None) == B.STATUS_BAD_BLOCK
+    assert fl(None, None, None, 0, 0, blk, None, None, None, None) == B.STATUS_OK
     # calibration copy
     cp = lib.equarx_calib_copy
     assert cp(A, A + 0x1000, 0, None) == B.STATUS_OK

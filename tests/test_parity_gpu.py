@@ -417,3 +417,80 @@ def test_variant_error_ordering_as_in_the_paper(gpu, oracle):
     full, semi, ag_only = mse(0), mse(eq.SEMI_LOOP), mse(eq.RS_UNQUANTIZED)
     assert ag_only < semi < full
     assert 0.0014 / 1.5 < full < 0.0014 * 1.5 and 0.001 / 1.5 < semi < 0.001 * 1.5 and 0.0003 / 1.5 < ag_only < 0.0003 * 1.5
+
+
+# ----------------------------------------------------------------------------- flat one-shot reduce
+
+def _flat_case(gpu, oracle, R, n, B, kind, seed):
+    local = gpu.bf16_of(_values(kind, n, seed))
+    remote = [gpu.bf16_of(_values(kind, n, seed + 1 + r)) for r in range(R)]
+    q = [oracle.quantize_bf16(x, B) for x in remote]
+    want_out, want_c, want_s = oracle.reduce_flat(local, [c for c, _ in q], [s for _, s in q], B)
+    # the senders' quantization runs on the GPU too (equarx_quantize), as in the real pipeline
+    dl = gpu.dev_bf16(local)
+    dc, ds = [], []
+    nb = eq.num_blocks(n, B)
+    for x in remote:
+        c = torch.empty(n, dtype=torch.int8, device="cuda")
+        s_ = torch.empty(max(nb, 1), dtype=torch.float32, device="cuda")
+        eq.equarx_quantize(gpu.dev_bf16(x), B, c, s_)
+        dc.append(c)
+        ds.append(s_)
+    out = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
+    co = torch.full((n,), 99, dtype=torch.int8, device="cuda")
+    so = torch.full((max(nb, 1),), -7.0, dtype=torch.float32, device="cuda")
+    eq.equarx_reduce_flat(dl, dc, ds, B, out, co, so)
+    torch.cuda.synchronize()
+    assert (gpu.host_u16(out) == want_out).all(), (R, n, B, kind)
+    assert (co.cpu().numpy() == want_c).all() and (so.cpu().numpy()[:nb].view(np.uint32) == want_s.view(np.uint32)).all()
+    # each output alone
+    out2 = torch.full_like(out, 3.0)
+    eq.equarx_reduce_flat(dl, dc, ds, B, out2)
+    co2, so2 = torch.full_like(co, 98), torch.full_like(so, -3.0)
+    eq.equarx_reduce_flat(dl, dc, ds, B, None, co2, so2)
+    torch.cuda.synchronize()
+    assert torch.equal(out2.view(torch.int16), out.view(torch.int16)) and torch.equal(co2, co) and torch.equal(so2[:nb], so[:nb])
+
+
+@pytest.mark.parametrize("B", BLOCKS)
+def test_flat_parity(gpu, oracle, B):
+    for i, (R, n, kind) in enumerate([(7, 4096, "normal"), (0, 3000, "normal"), (1, 8192 * 2 + 2048 + 13, "lognormal"),
+                                      (3, 8192 * 3 + 512, "student"), (15, 64 * 5376 // 2, "normal"), (7, 100, "tiny"),
+                                      (63, 2048 + 9, "normal"), (5, 8192 + 1, "sparse")]):
+        _flat_case(gpu, oracle, R, n, B, kind, 5000 + 100 * i)
+
+
+def test_flat_workload_shape(gpu, oracle):
+    w = wl.WORKLOADS["c3_gemma3_27b"].with_rows(48)
+    parts = [wl.as_u16(p) for p in wl.make_partials(w)]
+    q = [oracle.quantize_bf16(x, w.block) for x in parts[1:]]
+    want, _, _ = oracle.reduce_flat(parts[0], [c for c, _ in q], [s for _, s in q], w.block)
+    dc = [torch.from_numpy(c).cuda() for c, _ in q]
+    ds = [torch.from_numpy(s).cuda() for _, s in q]
+    out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_flat(gpu.dev_bf16(parts[0]), dc, ds, w.block, out)
+    torch.cuda.synchronize()
+    assert (gpu.host_u16(out) == want).all()
+    # two quantizations per value instead of eight: lower error than the ring's chain on the same data
+    ref = sum(oracle.bf16_to_f32(p).astype(np.float64) for p in parts)
+    err_flat = np.mean((oracle.bf16_to_f32(want).astype(np.float64) - ref) ** 2)
+    err_ring = np.mean((oracle.bf16_to_f32(oracle.reduce_chain(parts, w.block)).astype(np.float64) - ref) ** 2)
+    assert err_flat < err_ring
+
+
+def test_flat_bad_arguments(gpu):
+    x = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(4096, dtype=torch.int8, device="cuda")
+    s = torch.zeros(16, dtype=torch.float32, device="cuda")
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_flat(x, [c], [s], 256)                       # no output at all
+    assert e.value.status == eq.STATUS_NULL_POINTER
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_flat(x, [c], [s], 256, x)                    # out aliases the local shard
+    assert e.value.status == eq.STATUS_BAD_SHAPE
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_flat(x, [c], [s], 256, None, c, torch.zeros_like(s))   # codes_out aliases an input
+    assert e.value.status == eq.STATUS_BAD_SHAPE
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_flat(x, [c] * 64, [s] * 64, 256, torch.empty_like(x))
+    assert e.value.status == eq.STATUS_BAD_SHAPE
