@@ -146,6 +146,56 @@ def main() -> int:
         fused_kernel_ms = statistics.fmean(a.elapsed_time(b) for a, b in fused_pairs)
         out_fused = out.clone()
 
+        # all-to-all form: every non-owner quantizes its shard once, the owner reduces all of them in one kernel
+        flat_info = None
+        if P > 1:
+            qc = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(P - 1)]
+            qs = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(P - 1)]
+
+            def flat_pipeline(parts):
+                for r in range(P - 1):
+                    eq.equarx_quantize(parts[r + 1], B, qc[r], qs[r])
+                eq.equarx_reduce_flat(parts[0], qc, qs, B, out)
+
+            for k in range(W):
+                flat_pipeline(sets[k % 2])
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for k in range(K):
+                flat_pipeline(sets[k % 2])
+            torch.cuda.synchronize()
+            flat_ms = (time.perf_counter() - t0) * 1e3 / K
+            fp = []
+            for _ in range(min(K, 50)):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                b.record(stream)
+                fp.append((a, b))
+            torch.cuda.synchronize()
+            for k, (a, b) in enumerate(fp):
+                eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
+                eq.equarx_reduce_flat(sets[k % 2][0], qc, qs, B, out)
+            torch.cuda.synchronize()
+            flat_kernel_ms = statistics.fmean(a.elapsed_time(b) for a, b in fp)
+            flat_kernel_bytes = n * (2.0 + (P - 1) * (1.0 + 4.0 / B) + 2.0)
+            flat_pipe_bytes = flat_kernel_bytes + (P - 1) * n * (2.0 + 1.0 + 4.0 / B)
+            ref = torch.zeros(n, dtype=torch.float64, device="cuda")
+            flat_pipeline(sets[0])
+            for p in sets[0]:
+                ref += p.double()
+            flat_rel = float((out.double() - ref).norm() / ref.norm())
+            del ref
+            flat_info = {
+                "schedule": "all-to-all form: P-1 quantize launches, then one flat reduce + requantize kernel",
+                "ms_per_step": round(flat_ms, 5),
+                "effective_input_GBps": round(2.0 * P * n / (flat_ms * 1e-3) / 1e9, 1),
+                "algorithmic_bytes": flat_pipe_bytes,
+                "frac_of_hbm_peak": round(flat_pipe_bytes / (flat_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "flat_kernel_avg_launch_us": round(flat_kernel_ms * 1e3, 3),
+                "flat_kernel_frac_of_hbm_peak": round(flat_kernel_bytes / (flat_kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "rel_l2_vs_exact_sum": flat_rel,
+            }
+
         # error of the result against the exact sum (fp64), computed with torch on the GPU
         eq.equarx_reduce_fused(sets[0], B, out_fused)
         eq.equarx_reduce_quantized(sets[0], B, out, work)
@@ -255,7 +305,7 @@ def main() -> int:
         "config": {"workload": w.name, "P": P, "rows": w.rows, "hidden": w.hidden, "n": n, "block": B,
                    "distribution": w.dist, "schedule": chosen["schedule"]},
         "chain": chosen,
-        "other_schedule": other,
+        "other_schedules": [x for x in (other, flat_info) if x],
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": per_launch, "avg_launch_us": round(kernel_ms * 1e3, 3),
