@@ -107,29 +107,44 @@ struct ChainGrid {
     int64_t shard_elems;
 };
 
-inline ChainGrid chain_grid(int64_t n, int32_t block, int32_t P, bool ring)
+inline ChainGrid chain_grid(int64_t n, int32_t block, int32_t P, bool ring, int tiles)
 {
     ChainGrid g;
     if (ring) {
         const int64_t nb = blocks_of(n, block);
         g.shard_elems = (nb + P - 1) / P * block;           // ceil(nb / P) blocks per shard
-        g.x = grid_for(g.shard_elems, kTilesChain);
+        g.x = grid_for(g.shard_elems, tiles);
         g.y = (unsigned)P;
     } else {
         g.shard_elems = 0;
-        g.x = grid_for(n, kTilesChain);
+        g.x = grid_for(n, tiles);
         g.y = 1;
     }
     return g;
 }
 
-template <int B>
-void launch_chain(const PartialTable &tab, int P, int64_t n, bool rs, bool ag, bool ring, uint16_t *out,
-                  int8_t *wire_codes, float *wire_scales, int64_t c_step, int64_t s_step, hipStream_t s)
+// Which chain kernel a message gets, by its size in 2048-element tiles (measured on MI355X, P = 8 and 16):
+//   up to kChainSmallTiles     the latency-shaped kernel (one tile per workgroup, batched loads): 4.8 us vs 7.6 us
+//                              at 344 k elements;
+//   up to kChainMediumTiles    the bandwidth kernel with one tile per thread, so that every compute unit gets
+//                              work: 8.4 us vs 9.8 us at 2 M elements;
+//   above                      kTilesChain tiles per thread.
+#ifndef EQUARX_CHAIN_SMALL_MAX_TILES
+#define EQUARX_CHAIN_SMALL_MAX_TILES 512
+#endif
+#ifndef EQUARX_CHAIN_MEDIUM_MAX_TILES
+#define EQUARX_CHAIN_MEDIUM_MAX_TILES 2048
+#endif
+constexpr int64_t kChainSmallTiles = EQUARX_CHAIN_SMALL_MAX_TILES;
+constexpr int64_t kChainMediumTiles = EQUARX_CHAIN_MEDIUM_MAX_TILES;
+
+template <int B, int K>
+void launch_chain_k(const PartialTable &tab, int P, int64_t n, bool rs, bool ag, bool ring, uint16_t *out,
+                    int8_t *wire_codes, float *wire_scales, int64_t c_step, int64_t s_step, hipStream_t s)
 {
-    const ChainGrid g = chain_grid(n, B, P, ring);
-#define EQUARX_CHAIN(RS, AG, WIRE)                                                                                  \
-    launch2d(chain_kernel<B, kTilesChain, RS, AG, WIRE>, g.x, g.y, s, tab, P, n, g.shard_elems, out, wire_codes,   \
+    const ChainGrid g = chain_grid(n, B, P, ring, K);
+#define EQUARX_CHAIN(RS, AG, WIRE)                                                                        \
+    launch2d(chain_kernel<B, K, RS, AG, WIRE>, g.x, g.y, s, tab, P, n, g.shard_elems, out, wire_codes,   \
              wire_scales, c_step, s_step)
     if (rs && ag) {
         if (wire_codes) {
@@ -146,9 +161,28 @@ void launch_chain(const PartialTable &tab, int P, int64_t n, bool rs, bool ag, b
 }
 
 template <int B>
+void launch_chain(const PartialTable &tab, int P, int64_t n, bool rs, bool ag, bool ring, uint16_t *out,
+                  int8_t *wire_codes, float *wire_scales, int64_t c_step, int64_t s_step, hipStream_t s)
+{
+    const int64_t tiles = (n + kTileElems - 1) / kTileElems;
+    if (rs && ag && !ring && tiles <= kChainSmallTiles) {
+        const unsigned grid = grid_for(n, 1);
+        if (wire_codes) {
+            launch(chain_small_kernel<B, true>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step);
+        } else {
+            launch(chain_small_kernel<B, false>, grid, s, tab, P, n, out, wire_codes, wire_scales, c_step, s_step);
+        }
+    } else if (tiles <= kChainMediumTiles) {
+        launch_chain_k<B, 1>(tab, P, n, rs, ag, ring, out, wire_codes, wire_scales, c_step, s_step, s);
+    } else {
+        launch_chain_k<B, kTilesChain>(tab, P, n, rs, ag, ring, out, wire_codes, wire_scales, c_step, s_step, s);
+    }
+}
+
+template <int B>
 void launch_semi(const PartialTable &tab, int P, int64_t n, bool ag, bool ring, uint16_t *out, hipStream_t s)
 {
-    const ChainGrid g = chain_grid(n, B, P, ring);
+    const ChainGrid g = chain_grid(n, B, P, ring, kTilesChain);
     if (ag) {
         launch2d(semi_kernel<B, kTilesChain, true>, g.x, g.y, s, tab, P, n, g.shard_elems, out);
     } else {

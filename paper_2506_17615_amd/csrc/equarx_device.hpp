@@ -621,6 +621,79 @@ __global__ __launch_bounds__(kThreads) void chain_kernel(const PartialTable tab,
     }
 }
 
+// Small messages: the same chain, organised for latency instead of bandwidth.
+// With few tiles the bandwidth-shaped kernel leaves most compute units idle
+// and pays one memory round trip per hop.  Here a workgroup takes ONE tile and
+// requests the tiles of kSmallBatch partials at a time, two batches in flight
+// (one being consumed, one arriving), so a chain of P hops costs about P /
+// kSmallBatch round trips.  Every load is unconditional -- positions past the
+// last partial re-read the last partial and are ignored -- because a load
+// behind a condition makes the compiler wait for all outstanding loads where
+// the paths join.
+constexpr int kSmallBatch = 8;
+
+template <int B, bool kWire, bool kFull>
+__device__ __forceinline__ void chain_small_body(const PartialTable &tab, int P, int64_t n,
+                                                 uint16_t *__restrict__ out, int8_t *__restrict__ wire_codes,
+                                                 float *__restrict__ wire_scales, int64_t c_step, int64_t s_step,
+                                                 int64_t wg_at)
+{
+    constexpr int D = kSmallBatch;
+    const int lane_at = threadIdx.x * kLaneElems;
+    float t[1][8];
+    u32x4 a[D][1], b[D][1];
+
+#pragma unroll
+    for (int d = 0; d < D; ++d) load_tiles<1, kFull>(tab.x[d < P ? d : P - 1], wg_at, n, a[d]);
+
+    for (int base = 0; base < P; base += 2 * D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int i = base + D + d;
+            load_tiles<1, kFull>(tab.x[i < P ? i : P - 1], wg_at, n, b[d]);
+        }
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int i = base + d;
+            if (i == 0) {
+                widen_bf16x8(a[0][0], t[0]);
+            } else if (i < P) {
+                hop_tiles<B, 1, true, kWire, false, kFull>(t, a[d], wire_codes, wire_scales, c_step, s_step, i - 1,
+                                                           wg_at, n);
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int i = base + 2 * D + d;
+            load_tiles<1, kFull>(tab.x[i < P ? i : P - 1], wg_at, n, a[d]);
+        }
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int i = base + D + d;
+            if (i < P) {
+                hop_tiles<B, 1, true, kWire, false, kFull>(t, b[d], wire_codes, wire_scales, c_step, s_step, i - 1,
+                                                           wg_at, n);
+            }
+        }
+    }
+    finish_tile<B, true, kWire, kFull>(t[0], out, wire_codes, wire_scales, c_step, s_step, P - 1, wg_at + lane_at, n);
+}
+
+template <int B, bool kWire>
+__global__ __launch_bounds__(kThreads) void chain_small_kernel(const PartialTable tab, int P, int64_t n,
+                                                               uint16_t *__restrict__ out,
+                                                               int8_t *__restrict__ wire_codes,
+                                                               float *__restrict__ wire_scales, int64_t c_step,
+                                                               int64_t s_step)
+{
+    const int64_t wg_at = (int64_t)blockIdx.x * kTileElems;
+    if (wg_at + kTileElems <= n) {
+        chain_small_body<B, kWire, true>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, wg_at);
+    } else {
+        chain_small_body<B, kWire, false>(tab, P, n, out, wire_codes, wire_scales, c_step, s_step, wg_at);
+    }
+}
+
 // Semi-loop adder tree (Sec. 3.3).  Position 0 (device rot) owns the shard; the
 // other positions follow in ring order.  With h = P/2 the counter-clockwise
 // chain h+1, h+2, ..., P-1 and the clockwise chain h, h-1, ..., 1 each end in a

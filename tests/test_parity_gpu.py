@@ -154,6 +154,19 @@ def test_chain_parity_heavy_tails(gpu, oracle, B):
     _check_chain(gpu, oracle, parts, B)
 
 
+@pytest.mark.parametrize("tiles", (513, 600, 2048, 2049, 2300))
+def test_chain_parity_kernel_shapes(gpu, oracle, tiles):
+    """The single-launch chain picks its kernel by message size (small / one tile per thread / several):
+    lengths on both sides of the two thresholds, ragged, with the wire kept."""
+    n, B = 2048 * tiles - 2048 + 1500 + 3, 128
+    parts = [gpu.bf16_of(_values("lognormal", n, 700 + p)) for p in range(3)]
+    oracle.set_threads(8)
+    try:
+        _check_chain(gpu, oracle, parts, B)
+    finally:
+        oracle.set_threads(1)
+
+
 @pytest.mark.parametrize("P", (1, 2, 3, 64))
 def test_chain_lengths_of_chain(gpu, oracle, P):
     n, B = 2048 * 3 + 300, 64
@@ -257,6 +270,13 @@ def _sampled_blocks_check(gpu, oracle, w, n_sample=3000, seed=0):
     eq.equarx_reduce_quantized(dev, B, out2, None, wc, ws)
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+    wcf = torch.empty_like(wc)
+    wsf = torch.empty_like(ws)
+    eq.equarx_reduce_fused(dev, B, out_f, wcf, wsf)                             # single launch, wire kept
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out_f.view(torch.int16))
+    assert torch.equal(wcf[:, :n], wc[:, :n]) and torch.equal(wsf[:, :nb], ws[:, :nb])
+    del wcf, wsf
 
     rng = _rng(seed)
     blocks = np.unique(np.concatenate([[0, 1, nb - 2, nb - 1], rng.integers(0, nb, n_sample)]))
@@ -386,6 +406,18 @@ def test_variant_parity(gpu, oracle, name):
         got = gpu.gpu_variant(parts, B, flags)
         want = _oracle_variant(oracle, parts, B, flags)
         assert (got == want).all(), (name, P, n, B, kind, int((got != want).sum()))
+
+
+def test_variant_parity_large_message(gpu, oracle):
+    """Above the size where the chain kernels switch to several tiles per thread."""
+    P, n, B = 3, 2048 * 2100 + 2048 * 2 + 24, 256
+    parts = [gpu.bf16_of(_values("normal", n, 1300 + p)) for p in range(P)]
+    oracle.set_threads(8)
+    try:
+        for name, flags in VARIANT_FLAGS.items():
+            assert (gpu.gpu_variant(parts, B, flags) == _oracle_variant(oracle, parts, B, flags)).all(), name
+    finally:
+        oracle.set_threads(1)
 
 
 def test_variant_workloads(gpu, oracle):
