@@ -62,6 +62,18 @@ int equarx_quantize(const void *x_bf16, int64_t n, int32_t block,
                     int8_t *codes, float *scales, void *stream);
 
 /*
+ * equarx_quantize on `count` tensors of the same length n in one launch: what a
+ * device does before an all-to-all reduce-scatter, when it quantizes one shard
+ * per peer (see equarx_reduce_flat).  Tensor i: x_bf16[i] -> codes[i], scales[i].
+ *
+ *   x_bf16, codes, scales   HOST arrays of `count` device pointers
+ *                           (0 <= count <= EQUARX_MAX_PARTIALS), read before
+ *                           the call returns; no two tensors may share an output.
+ */
+int equarx_quantize_batch(const void *const *x_bf16, int8_t *const *codes, float *const *scales, int32_t count,
+                          int64_t n, int32_t block, void *stream);
+
+/*
  * Dequantize int8 codes to bf16 (Sec. 3.4: the dequantize that ends a
  * quantized all-gather).  out = bf16_rne(fp32(code) * scale[block of the
  * element]).

@@ -31,6 +31,8 @@ SEMI_LOOP, RS_UNQUANTIZED, AG_UNQUANTIZED, RING_ORDER = 1, 2, 4, 8
 _vp, _i64, _i32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
 SIGNATURES = {
     "equarx_quantize": (ctypes.c_int, [_vp, _i64, _i32, _vp, _vp, _vp]),
+    "equarx_quantize_batch": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i32, _i64,
+                                             _i32, _vp]),
     "equarx_dequantize": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp]),
     "equarx_reduce_stage": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "equarx_reduce_quantized": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp, _vp, _vp]),
@@ -127,6 +129,24 @@ def equarx_quantize(x_bf16: torch.Tensor, block: int, codes: torch.Tensor, scale
     _need(scales, torch.float32, num_blocks(n, block), "scales")
     _check(load().equarx_quantize(_ptr(x_bf16), x_bf16.numel(), block, _ptr(codes), _ptr(scales), _stream()),
            "equarx_quantize")
+
+
+def equarx_quantize_batch(xs, block: int, codes_list, scales_list) -> None:
+    """equarx_quantize on several bf16 tensors of equal length in one launch."""
+    count = len(xs)
+    if len(codes_list) != count or len(scales_list) != count:
+        raise ValueError("xs, codes_list and scales_list differ in length")
+    n = xs[0].numel() if count else 0
+    nb = num_blocks(n, block) if count else 0
+    for x, c, s in zip(xs, codes_list, scales_list):
+        _need(x, torch.bfloat16, n, "x_bf16")
+        if x.numel() != n:
+            raise ValueError("tensors differ in length")
+        _need(c, torch.int8, n, "codes")
+        _need(s, torch.float32, nb, "scales")
+    mk = lambda ts: (_vp * max(count, 1))(*[t.data_ptr() for t in ts])
+    _check(load().equarx_quantize_batch(mk(xs), mk(codes_list), mk(scales_list), count, n, block, _stream()),
+           "equarx_quantize_batch")
 
 
 def equarx_dequantize(codes: torch.Tensor, scales: torch.Tensor, block: int, out_bf16: torch.Tensor) -> None:

@@ -99,7 +99,7 @@ void launch_dequantize(const int8_t *codes, const float *scales, int64_t n, uint
 #define EQUARX_TILES_CHAIN 4
 #endif
 constexpr int kTilesChain = EQUARX_TILES_CHAIN;
-static_assert(kMaxPartials == EQUARX_MAX_PARTIALS, "header and device limit differ");
+static_assert(kMaxPartials == EQUARX_MAX_PARTIALS && kMaxBatch == EQUARX_MAX_PARTIALS, "header and device limits differ");
 
 // Shape of a chain launch: the whole tensor in array order, or (ring layout) one grid row per shard.
 struct ChainGrid {
@@ -312,6 +312,39 @@ int equarx_quantize(const void *x_bf16, int64_t n, int32_t block, int8_t *codes,
     if (!x_bf16 || !codes || !scales) return EQUARX_NULL_POINTER;
     if (misaligned(x_bf16, kAlign) || misaligned(codes, kAlign) || misaligned(scales, kAlign)) return EQUARX_MISALIGNED;
     do_quantize(x_bf16, n, block, codes, scales, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int equarx_quantize_batch(const void *const *x_bf16, int8_t *const *codes, float *const *scales, int32_t count,
+                          int64_t n, int32_t block, void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (count < 0 || count > kMaxBatch) return EQUARX_BAD_SHAPE;
+    if (count == 0 || n == 0) return EQUARX_OK;
+    if (!x_bf16 || !codes || !scales) return EQUARX_NULL_POINTER;
+    QuantizeBatch tab;
+    for (int32_t i = 0; i < kMaxBatch; ++i) {
+        tab.x[i] = nullptr;
+        tab.codes[i] = nullptr;
+        tab.scales[i] = nullptr;
+    }
+    for (int32_t i = 0; i < count; ++i) {
+        if (!x_bf16[i] || !codes[i] || !scales[i]) return EQUARX_NULL_POINTER;
+        if (misaligned(x_bf16[i], kAlign) || misaligned(codes[i], kAlign) || misaligned(scales[i], kAlign))
+            return EQUARX_MISALIGNED;
+        for (int32_t j = 0; j < i; ++j) {
+            if (codes[i] == codes[j] || scales[i] == scales[j]) return EQUARX_BAD_SHAPE;      // two tensors, one output
+        }
+        tab.x[i] = static_cast<const uint16_t *>(x_bf16[i]);
+        tab.codes[i] = codes[i];
+        tab.scales[i] = scales[i];
+    }
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+#define CALL(BB)                                                                                                     \
+    launch2d(quantize_batch_kernel<BB, kTilesQuantize>, grid_for(n, kTilesQuantize), (unsigned)count, hs, tab, n, \
+             blocks_of(n, BB))
+    EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
     return launch_status();
 }
 

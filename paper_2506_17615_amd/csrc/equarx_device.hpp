@@ -330,6 +330,31 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
     }
 }
 
+// Several tensors of the same length in one launch (blockIdx.y picks the
+// tensor): what a device does before an all-to-all, when it quantizes one shard
+// per peer.  One launch instead of one per shard spares the per-launch ramp.
+constexpr int kMaxBatch = 64;
+
+struct QuantizeBatch {
+    const uint16_t *x[kMaxBatch];
+    int8_t *codes[kMaxBatch];
+    float *scales[kMaxBatch];
+};
+
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void quantize_batch_kernel(const QuantizeBatch tab, int64_t n, int64_t nb)
+{
+    const uint16_t *x = tab.x[blockIdx.y];
+    int8_t *codes = tab.codes[blockIdx.y];
+    float *scales = tab.scales[blockIdx.y];
+    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
+    if (wg_at + kTileElems * K <= n) {
+        quantize_body<B, K, true>(x, n, codes, scales, nb, wg_at);
+    } else {
+        quantize_body<B, K, false>(x, n, codes, scales, nb, wg_at);
+    }
+}
+
 template <int B, int K, bool kFull>
 __device__ __forceinline__ void hop_body(const int8_t *cin, const float *sin, const uint16_t *__restrict__ x,
                                          int64_t n, int8_t *cout, float *sout, int64_t nb, int64_t wg_at)

@@ -132,6 +132,16 @@ def test_validation_rejects_before_launch(lib):
     assert rv(table(A, OUT, A, A), 4, n, blk, 9, OUT, None) == B.STATUS_BAD_SHAPE
     assert rv(ok4, 4, n, 96, 0, OUT, None) == B.STATUS_BAD_BLOCK
     assert rv(ok4, 4, 0, blk, 1, None, None) == B.STATUS_OK
+    qb = lib.equarx_quantize_batch
+    xs, cs, ss = table(A, A + 0x1000), table(A + 0x2000, A + 0x3000), table(A + 0x4000, A + 0x5000)
+    assert qb(xs, cs, ss, 65, n, blk, None) == B.STATUS_BAD_SHAPE
+    assert qb(xs, cs, ss, -1, n, blk, None) == B.STATUS_BAD_SHAPE
+    assert qb(None, cs, ss, 2, n, blk, None) == B.STATUS_NULL_POINTER
+    assert qb(table(A, 0), cs, ss, 2, n, blk, None) == B.STATUS_NULL_POINTER
+    assert qb(xs, table(A + 0x2000, ODD), ss, 2, n, blk, None) == B.STATUS_MISALIGNED
+    assert qb(xs, table(A + 0x2000, A + 0x2000), ss, 2, n, blk, None) == B.STATUS_BAD_SHAPE
+    assert qb(xs, cs, ss, 2, n, 5, None) == B.STATUS_BAD_BLOCK
+    assert qb(None, None, None, 0, n, blk, None) == B.STATUS_OK
     fl = lib.equarx_reduce_flat
     ctab, stab = table(A, A + 0x10000), table(A + 0x20000, A + 0x30000)
     assert fl(A + 0x40000, ctab, stab, 2, n, blk, None, None, None, None) == B.STATUS_NULL_POINTER

@@ -526,3 +526,25 @@ def test_flat_bad_arguments(gpu):
     with pytest.raises(eq.EquarxError) as e:
         eq.equarx_reduce_flat(x, [c] * 64, [s] * 64, 256, torch.empty_like(x))
     assert e.value.status == eq.STATUS_BAD_SHAPE
+
+
+@pytest.mark.parametrize("B", (32, 256))
+def test_quantize_batch_parity(gpu, oracle, B):
+    for count, n in ((7, 2048 * 7 + 300), (1, 4096), (64, 777), (3, 1 << 20)):
+        xs = [gpu.bf16_of(_values("lognormal", n, 8000 + i)) for i in range(count)]
+        nb = eq.num_blocks(n, B)
+        dx = [gpu.dev_bf16(x) for x in xs]
+        dc = [torch.full((n,), 99, dtype=torch.int8, device="cuda") for _ in range(count)]
+        ds = [torch.full((nb,), -7.0, dtype=torch.float32, device="cuda") for _ in range(count)]
+        eq.equarx_quantize_batch(dx, B, dc, ds)
+        torch.cuda.synchronize()
+        for i in range(count if n < (1 << 20) else 2):
+            c, s_ = oracle.quantize_bf16(xs[i], B)
+            assert (dc[i].cpu().numpy() == c).all() and (ds[i].cpu().numpy().view(np.uint32) == s_.view(np.uint32)).all()
+    eq.equarx_quantize_batch([], B, [], [])
+    x = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(4096, dtype=torch.int8, device="cuda")
+    s_ = torch.zeros(4096 // B, dtype=torch.float32, device="cuda")
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_quantize_batch([x, x], B, [c, c], [s_, torch.zeros_like(s_)])
+    assert e.value.status == eq.STATUS_BAD_SHAPE
