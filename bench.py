@@ -95,6 +95,8 @@ def main() -> int:
     from paper_2506_17615_amd import binding as eq
     from paper_2506_17615_amd import workloads as wl
 
+    from paper_2506_17615_amd import build as hip_build
+    hip_build.ensure_built()
     eq.load()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     w = wl.WORKLOADS[args.workload]

@@ -46,5 +46,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def ensure_built() -> str:
+    """Build only if no library is there at all (tests, smoke and bench call this; they never rebuild)."""
+    if not os.path.exists(LIB_PATH):
+        build(force=True)
+    return LIB_PATH
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -49,6 +49,8 @@ KINDS = ("normal", "lognormal", "student", "tiny", "huge", "sparse")
 def gpu():
     import gpu_util
     assert torch.cuda.is_available()
+    from paper_2506_17615_amd import build
+    build.ensure_built()        # builds only if no library is there; a missing library is otherwise an error
     eq.load()
     return gpu_util
 
@@ -548,3 +550,56 @@ def test_quantize_batch_parity(gpu, oracle, B):
     with pytest.raises(eq.EquarxError) as e:
         eq.equarx_quantize_batch([x, x], B, [c, c], [s_, torch.zeros_like(s_)])
     assert e.value.status == eq.STATUS_BAD_SHAPE
+
+
+# ----------------------------------------------------------------------------- streams, repetition, graphs
+
+def test_side_stream_and_repetition(gpu, oracle):
+    """Work is enqueued on the caller's stream, in order with what the caller put there; repeated calls give
+    the same bits."""
+    w = CHAIN_CASES["c4"]
+    host = wl.make_partials(w)
+    want = oracle.reduce_chain([wl.as_u16(p) for p in host], w.block)
+    side = torch.cuda.Stream()
+    outs = []
+    with torch.cuda.stream(side):
+        dev = [torch.empty(w.n, dtype=torch.bfloat16, device="cuda") for _ in host]
+        for d, p in zip(dev, host):
+            d.copy_(p.reshape(-1), non_blocking=True)          # the inputs arrive on the same stream
+        work = eq.alloc_workspace(w.P, w.n, w.block)
+        for rep in range(3):
+            out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+            if rep == 1:
+                eq.equarx_reduce_fused(dev, w.block, out)
+            else:
+                eq.equarx_reduce_quantized(dev, w.block, out, work)
+            outs.append(out)
+    side.synchronize()
+    for out in outs:
+        assert (gpu.host_u16(out) == want).all()
+
+
+def test_graph_capture_and_replay(gpu, oracle):
+    """The entry points only enqueue kernels, so a caller may capture them in a HIP graph.  Replays are checked
+    against the oracle after the inputs changed between replays."""
+    w = CHAIN_CASES["c2_rows24"]
+    n, B, P = w.n, w.block, w.P
+    dev = [torch.zeros(n, dtype=torch.bfloat16, device="cuda") for _ in range(P)]
+    out_a = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    out_b = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    work = eq.alloc_workspace(P, n, B)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        eq.equarx_reduce_quantized(dev, B, out_a, work)
+        eq.equarx_reduce_fused(dev, B, out_b)
+    for rep in range(3):
+        host = [gpu.bf16_of(_values("lognormal", n, 6000 + 10 * rep + p)) for p in range(P)]
+        for d, h in zip(dev, host):
+            d.copy_(gpu.dev_bf16(h))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.reduce_chain(host, B)
+        assert (gpu.host_u16(out_a) == want).all(), rep
+        assert (gpu.host_u16(out_b) == want).all(), rep
