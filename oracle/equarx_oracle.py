@@ -304,3 +304,58 @@ def reduce_ring(partials, B: int, semi: bool = False, quantize_rs: bool = True, 
         else:
             out[lo:hi] = reduce_stages([arrs[d][lo:hi] for d in ring_order(P, k)], B, quantize_rs, quantize_ag, lib=lib)
     return out
+
+
+# ---------------------------------------------------------------------------------------------------------
+# The paper's own block geometry (Sec. 3.2, "VPU-friendly"): a minishard of `chunks` consecutive chunks of
+# CHUNK = 8 x 128 = 1024 elements gets 1024 scales; scale j covers the elements at position j of every chunk,
+# i.e. a block of `chunks` entries 1024 apart.  Transposing each minishard from [chunks, 1024] to
+# [1024, chunks] turns those strided blocks into contiguous blocks of B = chunks, so every strided function
+# below IS the contiguous one applied between that transposition and its inverse; scale number
+# minishard * 1024 + j is then simply block number minishard * 1024 + j of the transposed tensor.
+
+CHUNK = 1024
+
+
+def _check_strided(n: int, chunks: int) -> None:
+    if chunks < 1 or n % (CHUNK * chunks) != 0:
+        raise ValueError("strided layout needs n to be a multiple of 1024 * chunks")
+
+
+def to_block_major(a, chunks: int) -> np.ndarray:
+    """[minishards, chunks, 1024] -> [minishards, 1024, chunks], flattened."""
+    a = np.asarray(a).reshape(-1)
+    _check_strided(a.size, chunks)
+    return np.ascontiguousarray(a.reshape(-1, chunks, CHUNK).transpose(0, 2, 1)).reshape(-1)
+
+
+def from_block_major(a, chunks: int) -> np.ndarray:
+    a = np.asarray(a).reshape(-1)
+    _check_strided(a.size, chunks)
+    return np.ascontiguousarray(a.reshape(-1, CHUNK, chunks).transpose(0, 2, 1)).reshape(-1)
+
+
+def quantize_bf16_strided(x_u16, chunks: int, lib=None):
+    c, s = quantize_bf16(to_block_major(_arr(x_u16, np.uint16), chunks), chunks, lib=lib)
+    return from_block_major(c, chunks), s
+
+
+def dequantize_bf16_strided(codes, scales, chunks: int, lib=None) -> np.ndarray:
+    out = dequantize_bf16(to_block_major(_arr(codes, np.int8), chunks), scales, chunks, lib=lib)
+    return from_block_major(out, chunks)
+
+
+def hop_strided(codes_in, scales_in, local_u16, chunks: int, lib=None):
+    c, s = hop(to_block_major(_arr(codes_in, np.int8), chunks), scales_in,
+               to_block_major(_arr(local_u16, np.uint16), chunks), chunks, lib=lib)
+    return from_block_major(c, chunks), s
+
+
+def reduce_chain_strided(partials, chunks: int, keep_wire: bool = False, lib=None):
+    """The full-loop chain (RS and AG quantized) with the strided block geometry."""
+    moved = [to_block_major(_arr(p, np.uint16), chunks) for p in partials]
+    if keep_wire:
+        out, wc, ws = reduce_chain(moved, chunks, keep_wire=True, lib=lib)
+        wc = np.stack([from_block_major(row, chunks) for row in wc])
+        return from_block_major(out, chunks), wc, ws
+    return from_block_major(reduce_chain(moved, chunks, lib=lib), chunks)

@@ -582,4 +582,54 @@ def pin_ring_order(lib=None):
     assert (got[lo:hi] == o.reduce_chain([parts[d][lo:hi] for d in (2, 3, 0, 1)], B)).all()
 
 
-ALL_PINS += [pin_stage_knobs, pin_semi_loop, pin_fig7_semi_loop, pin_flat, pin_ring_order]
+def pin_strided_geometry(lib=None):
+    """Sec. 3.2's own geometry: the paper's worked example (a shard of a (512,512) tensor on 4 devices is 64
+    chunks of 8x128, gets 1024 scales, block size 64), which element shares a scale with which, and scale and
+    codes of single positions computed directly from the definition."""
+    g = read_golden("sec32_block_example.txt")
+    shard = int(g["tensor_rows"] * g["tensor_cols"] / g["shards"])
+    chunk = int(g["chunk_rows"] * g["chunk_cols"])
+    chunks = shard // chunk
+    assert chunk == o.CHUNK and chunks == g["chunks_per_shard"] == g["block_size"]
+    rng = _rng(33)
+    x = _bf16(rng.standard_normal(shard).astype(np.float32))
+    c, s = o.quantize_bf16_strided(x, chunks, lib=lib)
+    assert s.size == g["scales_per_shard"] and c.size == shard
+    xf = bf16_bits_to_f32(x)
+    # scale j is decided by the 64 entries at position j of every chunk, and by nothing else
+    for j in (0, 1, 127, 128, 600, 1023):
+        members = xf[j::chunk]
+        assert members.size == g["block_size"]
+        codes, scale = _expected_block(members)
+        assert s[j] == scale and c[j::chunk].tolist() == codes
+    big = x.copy()
+    big[5 * chunk + 77] = _bf16(np.array([1000.0], np.float32))[0]
+    c2, s2 = o.quantize_bf16_strided(big, chunks, lib=lib)
+    changed = np.flatnonzero(s2 != s)
+    assert changed.tolist() == [77]
+    assert (np.flatnonzero(c2 != c) % chunk == 77).all() and c2[5 * chunk + 77] == 127
+    # m minishards: block 64/m, 1024 scales each (two minishards of 32 chunks here)
+    cm, sm = o.quantize_bf16_strided(x, chunks // 2, lib=lib)
+    assert sm.size == 2048
+    codes, scale = _expected_block(xf[32 * chunk + 9::chunk])
+    assert sm[1024 + 9] == scale and cm[32 * chunk + 9::chunk].tolist() == codes
+    # dequantize, hop and chain follow the same element -> scale map
+    d = o.dequantize_bf16_strided(c, s, chunks, lib=lib)
+    want = _bf16((c.astype(np.float32) * np.tile(s, chunks)).astype(np.float32))
+    assert (d == want).all()
+    y = _bf16(rng.standard_normal(shard).astype(np.float32))
+    ch, sh = o.hop_strided(c, s, y, chunks, lib=lib)
+    j = 300
+    t = _fma_exact(c[j::chunk].astype(np.float32), np.full(chunks, s[j], np.float32), bf16_bits_to_f32(y)[j::chunk])
+    codes, scale = _expected_block(t)
+    assert sh[j] == scale and ch[j::chunk].tolist() == codes
+    out, wc, ws = o.reduce_chain_strided([x, y], chunks, keep_wire=True, lib=lib)
+    assert (wc[0] == c).all() and (ws[0] == s).all() and (wc[1] == ch).all() and (ws[1] == sh).all()
+    assert (out == o.dequantize_bf16_strided(ch, sh, chunks, lib=lib)).all()
+    # the two transpositions are inverse permutations
+    idx = np.arange(shard)
+    assert (o.from_block_major(o.to_block_major(idx, chunks), chunks) == idx).all()
+    assert o.to_block_major(idx, chunks)[:3].tolist() == [0, 1024, 2048]
+
+
+ALL_PINS += [pin_stage_knobs, pin_semi_loop, pin_fig7_semi_loop, pin_flat, pin_ring_order, pin_strided_geometry]
