@@ -206,6 +206,35 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
                        int64_t n, int32_t block, void *out_bf16, int8_t *codes_out, float *scales_out,
                        void *stream);
 
+/*
+ * The paper's own block geometry (Sec. 3.2, "VPU-friendly" quantization).
+ *
+ * The tensor is a sequence of chunks of 1024 elements (8 x 128, the TPU vector
+ * register, contiguous in its tiled layout); a minishard is `chunks`
+ * consecutive chunks and gets 1024 scales: scale j of a minishard comes from
+ * the max-abs over position j of each of its chunks, so a quantization block
+ * is the `chunks` elements  m*1024*chunks + c*1024 + j,  c = 0 .. chunks-1,
+ * and its scale is scales[m*1024 + j].  (The paper's example: a shard of 64
+ * chunks, 1024 scales, block size 64; with m minishards per shard, 64/m.)
+ * Arithmetic exactly as in the contiguous entry points of the same name; only
+ * the element -> block map differs.
+ *
+ *   chunks   32, 64 or 128 (else EQUARX_BAD_BLOCK); n must be a multiple of
+ *            1024 * chunks (else EQUARX_BAD_SHAPE).  scales has n / chunks entries.
+ *   equarx_reduce_quantized_strided: the hop-by-hop chain (P+1 launches);
+ *            workspace of equarx_workspace_bytes(P, n, chunks) bytes, 256-byte aligned.
+ *   equarx_reduce_stage_strided: codes_out / scales_out may alias the inputs.
+ */
+int equarx_quantize_strided(const void *x_bf16, int64_t n, int32_t chunks,
+                            int8_t *codes, float *scales, void *stream);
+int equarx_dequantize_strided(const int8_t *codes, const float *scales, int64_t n, int32_t chunks,
+                              void *out_bf16, void *stream);
+int equarx_reduce_stage_strided(const int8_t *codes_in, const float *scales_in, const void *local_bf16,
+                                int64_t n, int32_t chunks,
+                                int8_t *codes_out, float *scales_out, void *stream);
+int equarx_reduce_quantized_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
+                                    void *out_bf16, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Bytes of workspace equarx_reduce_quantized needs (0 for invalid arguments). */
 size_t equarx_workspace_bytes(int32_t P, int64_t n, int32_t block);
 

@@ -40,6 +40,10 @@ SIGNATURES = {
     "equarx_reduce_variant": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp]),
     "equarx_reduce_flat": (ctypes.c_int, [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp,
                                           _vp]),
+    "equarx_quantize_strided": (ctypes.c_int, [_vp, _i64, _i32, _vp, _vp, _vp]),
+    "equarx_dequantize_strided": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp]),
+    "equarx_reduce_stage_strided": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp]),
+    "equarx_reduce_quantized_strided": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp]),
     "equarx_workspace_bytes": (_sz, [_i32, _i64, _i32]),
     "equarx_num_blocks": (_i64, [_i64, _i32]),
     "equarx_wire_row_codes": (_i64, [_i64]),
@@ -243,6 +247,60 @@ def equarx_reduce_flat(local_bf16, codes_list, scales_list, block: int, out_bf16
     stab = (_vp * max(R, 1))(*[s.data_ptr() for s in scales_list])
     _check(load().equarx_reduce_flat(_ptr(local_bf16), ctab, stab, R, n, block, _ptr(out_bf16), _ptr(codes_out),
                                      _ptr(scales_out), _stream()), "equarx_reduce_flat")
+
+
+STRIDED_CHUNKS = (32, 64, 128)
+
+
+def _strided_scales(n: int, chunks: int) -> int:
+    return n // chunks if chunks in STRIDED_CHUNKS else 0
+
+
+def equarx_quantize_strided(x_bf16, chunks: int, codes, scales) -> None:
+    """Q with the strided block geometry: scale m*1024+j covers position j of every chunk of minishard m."""
+    n = x_bf16.numel()
+    _need(x_bf16, torch.bfloat16, n, "x_bf16")
+    _need(codes, torch.int8, n, "codes")
+    _need(scales, torch.float32, _strided_scales(n, chunks), "scales")
+    _check(load().equarx_quantize_strided(_ptr(x_bf16), n, chunks, _ptr(codes), _ptr(scales), _stream()),
+           "equarx_quantize_strided")
+
+
+def equarx_dequantize_strided(codes, scales, chunks: int, out_bf16) -> None:
+    n = codes.numel()
+    _need(codes, torch.int8, n, "codes")
+    _need(scales, torch.float32, _strided_scales(n, chunks), "scales")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    _check(load().equarx_dequantize_strided(_ptr(codes), _ptr(scales), n, chunks, _ptr(out_bf16), _stream()),
+           "equarx_dequantize_strided")
+
+
+def equarx_reduce_stage_strided(codes_in, scales_in, local_bf16, chunks: int, codes_out, scales_out) -> None:
+    n = local_bf16.numel()
+    ns = _strided_scales(n, chunks)
+    _need(local_bf16, torch.bfloat16, n, "local_bf16")
+    _need(codes_in, torch.int8, n, "codes_in")
+    _need(codes_out, torch.int8, n, "codes_out")
+    _need(scales_in, torch.float32, ns, "scales_in")
+    _need(scales_out, torch.float32, ns, "scales_out")
+    _check(load().equarx_reduce_stage_strided(_ptr(codes_in), _ptr(scales_in), _ptr(local_bf16), n, chunks,
+                                              _ptr(codes_out), _ptr(scales_out), _stream()), "equarx_reduce_stage_strided")
+
+
+def equarx_reduce_quantized_strided(partials, chunks: int, out_bf16, workspace) -> None:
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+        if p.numel() != n:
+            raise ValueError("partials differ in length")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    if workspace is not None and not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace: need a contiguous CUDA tensor")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().equarx_reduce_quantized_strided(table, P, n, chunks, _ptr(out_bf16), _ptr(workspace), ws_bytes,
+                                                  _stream()), "equarx_reduce_quantized_strided")
 
 
 def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:

@@ -10,7 +10,8 @@ CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_PKG, "libequarx.so")
 SOURCES = [os.path.join(CSRC, "equarx_api.hip")]
-HEADERS = [os.path.join(CSRC, "equarx_device.hpp"), os.path.join(INCLUDE, "equarx.h")]
+HEADERS = [os.path.join(CSRC, "equarx_device.hpp"), os.path.join(CSRC, "equarx_strided.hpp"),
+           os.path.join(INCLUDE, "equarx.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",

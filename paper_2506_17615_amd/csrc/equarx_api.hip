@@ -5,6 +5,7 @@
 #include <hip/hip_ext.h>
 
 #include "equarx_device.hpp"
+#include "equarx_strided.hpp"
 
 namespace {
 
@@ -253,6 +254,52 @@ void do_dequantize(const int8_t *codes, const float *scales, int64_t n, int32_t 
 #define CALL(BB) launch_dequantize<BB>(codes, scales, n, static_cast<uint16_t *>(out), s)
     EQUARX_DISPATCH_BLOCK(block, CALL)
 #undef CALL
+}
+
+// ---- strided (Sec. 3.2) geometry ----
+
+inline int check_strided(int64_t n, int32_t chunks)
+{
+    if (chunks != 32 && chunks != 64 && chunks != 128) return EQUARX_BAD_BLOCK;
+    if (n < 0 || too_long(n) || n % ((int64_t)kChunk * chunks) != 0) return EQUARX_BAD_SHAPE;
+    return EQUARX_OK;
+}
+
+inline unsigned strided_grid(int64_t n, int32_t chunks)
+{
+    return (unsigned)(n / ((int64_t)kChunk * chunks) * kSlicesPerChunk);
+}
+
+#define EQUARX_DISPATCH_CHUNKS(chunks, CALL) \
+    switch (chunks) {                        \
+        case 32: CALL(4); break;             \
+        case 64: CALL(8); break;             \
+        case 128: CALL(16); break;           \
+        default: break;                      \
+    }
+
+void do_quantize_strided(const void *x, int64_t n, int32_t chunks, int8_t *codes, float *scales, hipStream_t s)
+{
+#define CALL(RR) \
+    launch(quantize_strided_kernel<RR>, strided_grid(n, chunks), s, static_cast<const uint16_t *>(x), codes, scales)
+    EQUARX_DISPATCH_CHUNKS(chunks, CALL)
+#undef CALL
+}
+
+void do_hop_strided(const int8_t *cin, const float *sin, const void *x, int64_t n, int32_t chunks, int8_t *cout,
+                    float *sout, hipStream_t s)
+{
+#define CALL(RR) \
+    launch(hop_strided_kernel<RR>, strided_grid(n, chunks), s, cin, sin, static_cast<const uint16_t *>(x), cout, sout)
+    EQUARX_DISPATCH_CHUNKS(chunks, CALL)
+#undef CALL
+}
+
+void do_dequantize_strided(const int8_t *codes, const float *scales, int64_t n, int32_t chunks, void *out,
+                           hipStream_t s)
+{
+    launch(dequantize_strided_kernel<kTilesDequantize>, grid_for(n, kTilesDequantize), s, codes, scales, n, (int)chunks,
+           static_cast<uint16_t *>(out));
 }
 
 inline int check_shape(int64_t n, int32_t block)
@@ -515,6 +562,70 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
                     scales_out, hs)
     EQUARX_DISPATCH_BLOCK(block, CALL)
 #undef CALL
+    return launch_status();
+}
+
+int equarx_quantize_strided(const void *x_bf16, int64_t n, int32_t chunks, int8_t *codes, float *scales, void *stream)
+{
+    if (int st = check_strided(n, chunks)) return st;
+    if (n == 0) return EQUARX_OK;
+    if (!x_bf16 || !codes || !scales) return EQUARX_NULL_POINTER;
+    if (misaligned(x_bf16, kAlign) || misaligned(codes, kAlign) || misaligned(scales, kAlign)) return EQUARX_MISALIGNED;
+    do_quantize_strided(x_bf16, n, chunks, codes, scales, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int equarx_dequantize_strided(const int8_t *codes, const float *scales, int64_t n, int32_t chunks, void *out_bf16,
+                              void *stream)
+{
+    if (int st = check_strided(n, chunks)) return st;
+    if (n == 0) return EQUARX_OK;
+    if (!codes || !scales || !out_bf16) return EQUARX_NULL_POINTER;
+    if (misaligned(codes, kAlign) || misaligned(scales, kAlign) || misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
+    do_dequantize_strided(codes, scales, n, chunks, out_bf16, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int equarx_reduce_stage_strided(const int8_t *codes_in, const float *scales_in, const void *local_bf16, int64_t n,
+                                int32_t chunks, int8_t *codes_out, float *scales_out, void *stream)
+{
+    if (int st = check_strided(n, chunks)) return st;
+    if (n == 0) return EQUARX_OK;
+    if (!codes_in || !scales_in || !local_bf16 || !codes_out || !scales_out) return EQUARX_NULL_POINTER;
+    if (misaligned(codes_in, kAlign) || misaligned(scales_in, kAlign) || misaligned(local_bf16, kAlign) ||
+        misaligned(codes_out, kAlign) || misaligned(scales_out, kAlign))
+        return EQUARX_MISALIGNED;
+    do_hop_strided(codes_in, scales_in, local_bf16, n, chunks, codes_out, scales_out, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+int equarx_reduce_quantized_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
+                                    void *out_bf16, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int st = check_strided(n, chunks)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16 || !workspace) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign) || misaligned(workspace, kWorkspaceAlign)) return EQUARX_MISALIGNED;
+    for (int32_t i = 0; i < P; ++i) {
+        if (!partials_bf16[i]) return EQUARX_NULL_POINTER;
+        if (misaligned(partials_bf16[i], kAlign)) return EQUARX_MISALIGNED;
+        if (partials_bf16[i] == out_bf16) return EQUARX_BAD_SHAPE;
+    }
+    // one scale per `chunks` elements: the same workspace as the contiguous chain with block = chunks
+    if (workspace_bytes < equarx_workspace_bytes(P, n, chunks)) return EQUARX_WORKSPACE_TOO_SMALL;
+    const size_t codes = round_up((size_t)n, kWorkspaceAlign);
+    const size_t scales = round_up((size_t)(n / chunks) * sizeof(float), kWorkspaceAlign);
+    char *w = static_cast<char *>(workspace);
+    int8_t *c[2] = {reinterpret_cast<int8_t *>(w), reinterpret_cast<int8_t *>(w + codes + scales)};
+    float *s[2] = {reinterpret_cast<float *>(w + codes), reinterpret_cast<float *>(w + 2 * codes + scales)};
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    do_quantize_strided(partials_bf16[0], n, chunks, c[0], s[0], hs);
+    for (int32_t i = 1; i < P; ++i) {
+        do_hop_strided(c[(i - 1) & 1], s[(i - 1) & 1], partials_bf16[i], n, chunks, c[i & 1], s[i & 1], hs);
+    }
+    do_dequantize_strided(c[(P - 1) & 1], s[(P - 1) & 1], n, chunks, out_bf16, hs);
     return launch_status();
 }
 

@@ -1,0 +1,217 @@
+// The paper's own block geometry on gfx950 (EQuARX, arXiv 2506.17615, Sec. 3.2).
+//
+// There a shard is cut into chunks of 8 x 128 = 1024 elements (the TPU's vector
+// register shape, contiguous in its tiled memory layout) and a minishard of
+// `chunks` consecutive chunks gets 1024 scales: scale j comes from the max-abs
+// over position j of every chunk, so a quantization block is `chunks` entries
+// that lie 1024 elements apart.  On the TPU this avoids any reduction inside a
+// vector register.  On a GPU it means the opposite of the contiguous layout:
+// no cross-lane work at all (a lane keeps its own 8 positions), but a
+// reduction ACROSS the chunks of a minishard.
+//
+// Decomposition: a workgroup of 256 threads takes one slice of 256 positions of
+// one minishard.  Thread (g, l), g = 0..7, l = 0..31, owns positions 8l..8l+7
+// of the slice in chunks g, g+8, g+16, ...; it keeps the raw inputs of its
+// chunks/8 chunks in registers, so global memory is read once.  The 8 partial
+// maxima per position meet in LDS (8 KiB), every thread derives the scales of
+// its 8 positions, recomputes its values from the registers, scales, rounds
+// and stores.  Loads of a half-wave cover 512 contiguous bytes.
+#pragma once
+
+#include "equarx_device.hpp"
+
+namespace equarx {
+
+constexpr int kChunk = 1024;                               // elements per chunk (8 x 128)
+constexpr int kSliceLanes = 32;                            // lanes across a slice of a chunk
+constexpr int kSlicePos = kSliceLanes * kLaneElems;        // 256 positions per workgroup
+constexpr int kChunkGroups = kThreads / kSliceLanes;       // 8 groups of lanes, each walking every 8th chunk
+constexpr int kSlicesPerChunk = kChunk / kSlicePos;        // 4 workgroups per minishard
+static_assert(kThreads == 256, "the strided kernels are laid out for 256-thread workgroups");
+
+struct StridedSpot {
+    int64_t elem;       // first element of the lane in chunk `g` of its minishard
+    int64_t scale;      // index of the lane's first scale
+    int g;              // chunk group
+};
+
+__device__ __forceinline__ StridedSpot strided_spot(int chunks)
+{
+    StridedSpot sp;
+    const int l = threadIdx.x % kSliceLanes;
+    sp.g = threadIdx.x / kSliceLanes;
+    const int64_t ms = blockIdx.x / kSlicesPerChunk;
+    const int pos = (blockIdx.x % kSlicesPerChunk) * kSlicePos + l * kLaneElems;
+    sp.elem = ms * ((int64_t)kChunk * chunks) + (int64_t)sp.g * kChunk + pos;
+    sp.scale = ms * kChunk + pos;
+    return sp;
+}
+
+// Max over the 8 chunk groups for each of the lane's 8 positions, through LDS.
+// m: bit patterns of non-negative floats.  Every thread of the workgroup calls this.
+__device__ __forceinline__ void across_chunks_max(uint32_t (&m)[8], uint32_t (*red)[kSlicePos])
+{
+    const int l = threadIdx.x % kSliceLanes;
+    const int g = threadIdx.x / kSliceLanes;
+    __syncthreads();                                        // the previous round's readers are done
+    u32x4 *row = reinterpret_cast<u32x4 *>(&red[g][l * kLaneElems]);
+    row[0] = u32x4{m[0], m[1], m[2], m[3]};
+    row[1] = u32x4{m[4], m[5], m[6], m[7]};
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < kChunkGroups; ++h) {
+        const u32x4 *other = reinterpret_cast<const u32x4 *>(&red[h][l * kLaneElems]);
+        const u32x4 a = other[0], b = other[1];
+        m[0] = umax(m[0], a.x); m[1] = umax(m[1], a.y); m[2] = umax(m[2], a.z); m[3] = umax(m[3], a.w);
+        m[4] = umax(m[4], b.x); m[5] = umax(m[5], b.y); m[6] = umax(m[6], b.z); m[7] = umax(m[7], b.w);
+    }
+}
+
+__device__ __forceinline__ void note_absmax(const float (&t)[8], uint32_t (&m)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m[j] = umax(m[j], __float_as_uint(t[j]) & 0x7FFFFFFFu);
+}
+
+__device__ __forceinline__ u32x2 scale_and_pack(const float (&t)[8], const float (&inv)[8])
+{
+    float r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = __builtin_rintf(t[j] * inv[j]);
+    return pack_codes(r);
+}
+
+// R = chunks / 8 chunks per thread.
+template <int R>
+__global__ __launch_bounds__(kThreads) void quantize_strided_kernel(const uint16_t *__restrict__ x,
+                                                                    int8_t *__restrict__ codes,
+                                                                    float *__restrict__ scales)
+{
+    __shared__ uint32_t red[kChunkGroups][kSlicePos];
+    constexpr int chunks = R * kChunkGroups;
+    const StridedSpot sp = strided_spot(chunks);
+
+    u32x4 xv[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        xv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(x + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+    }
+    uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float t[8];
+        widen_bf16x8(xv[r], t);
+        note_absmax(t, m);
+    }
+    across_chunks_max(m, red);
+
+    float scale[8], inv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) block_quotients(__uint_as_float(m[j]), scale[j], inv[j]);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float t[8];
+        widen_bf16x8(xv[r], t);
+        *reinterpret_cast<u32x2 *>(codes + sp.elem + (int64_t)r * kChunkGroups * kChunk) = scale_and_pack(t, inv);
+    }
+    if (sp.g == 0) {
+        float *s = scales + sp.scale;
+        *reinterpret_cast<u32x4 *>(s) = u32x4{__float_as_uint(scale[0]), __float_as_uint(scale[1]),
+                                              __float_as_uint(scale[2]), __float_as_uint(scale[3])};
+        *reinterpret_cast<u32x4 *>(s + 4) = u32x4{__float_as_uint(scale[4]), __float_as_uint(scale[5]),
+                                                  __float_as_uint(scale[6]), __float_as_uint(scale[7])};
+    }
+}
+
+// One hop in the strided geometry.  Output wire may be the input wire: a
+// workgroup holds all its inputs in registers before it stores anything.
+template <int R>
+__global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin, const float *sin,
+                                                               const uint16_t *__restrict__ x, int8_t *cout,
+                                                               float *sout)
+{
+    __shared__ uint32_t red[kChunkGroups][kSlicePos];
+    constexpr int chunks = R * kChunkGroups;
+    const StridedSpot sp = strided_spot(chunks);
+
+    u32x4 xv[R];
+    u32x2 cv[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int64_t at = sp.elem + (int64_t)r * kChunkGroups * kChunk;
+        xv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(x + at));
+        cv[r] = *reinterpret_cast<const u32x2 *>(cin + at);
+    }
+    float s_in[8];
+    {
+        const u32x4 a = *reinterpret_cast<const u32x4 *>(sin + sp.scale);
+        const u32x4 b = *reinterpret_cast<const u32x4 *>(sin + sp.scale + 4);
+        s_in[0] = __uint_as_float(a.x); s_in[1] = __uint_as_float(a.y);
+        s_in[2] = __uint_as_float(a.z); s_in[3] = __uint_as_float(a.w);
+        s_in[4] = __uint_as_float(b.x); s_in[5] = __uint_as_float(b.y);
+        s_in[6] = __uint_as_float(b.z); s_in[7] = __uint_as_float(b.w);
+    }
+
+    uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float xf[8], qf[8], t[8];
+        widen_bf16x8(xv[r], xf);
+        widen_i8x8(cv[r], qf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(qf[j], s_in[j], xf[j]);
+        note_absmax(t, m);
+    }
+    across_chunks_max(m, red);
+
+    float scale[8], inv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) block_quotients(__uint_as_float(m[j]), scale[j], inv[j]);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float xf[8], qf[8], t[8];
+        widen_bf16x8(xv[r], xf);
+        widen_i8x8(cv[r], qf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(qf[j], s_in[j], xf[j]);      // same operands, same bits
+        *reinterpret_cast<u32x2 *>(cout + sp.elem + (int64_t)r * kChunkGroups * kChunk) = scale_and_pack(t, inv);
+    }
+    if (sp.g == 0) {
+        float *s = sout + sp.scale;
+        *reinterpret_cast<u32x4 *>(s) = u32x4{__float_as_uint(scale[0]), __float_as_uint(scale[1]),
+                                              __float_as_uint(scale[2]), __float_as_uint(scale[3])};
+        *reinterpret_cast<u32x4 *>(s + 4) = u32x4{__float_as_uint(scale[4]), __float_as_uint(scale[5]),
+                                                  __float_as_uint(scale[6]), __float_as_uint(scale[7])};
+    }
+}
+
+// Dequantize in the strided geometry: element e uses scale (e / (1024*chunks)) * 1024 + e % 1024, so the 8
+// elements of a lane use 8 consecutive scales.  n is a multiple of 1024, hence of the 2048-element tile.
+template <int K>
+__global__ __launch_bounds__(kThreads) void dequantize_strided_kernel(const int8_t *__restrict__ codes,
+                                                                      const float *__restrict__ scales, int64_t n,
+                                                                      int chunks, uint16_t *__restrict__ out)
+{
+    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
+    const int lane_at = threadIdx.x * kLaneElems;
+    const int64_t minishard = (int64_t)kChunk * chunks;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        if (at >= n) continue;                       // n % 8 == 0: a lane is inside or outside as a whole
+        const u32x2 cv = *reinterpret_cast<const u32x2 *>(codes + at);
+        const float *s = scales + (at / minishard) * kChunk + at % kChunk;
+        const u32x4 a = *reinterpret_cast<const u32x4 *>(s);
+        const u32x4 b = *reinterpret_cast<const u32x4 *>(s + 4);
+        float qf[8];
+        widen_i8x8(cv, qf);
+        u32x4 w;
+        w.x = narrow_bf16x2(qf[0] * __uint_as_float(a.x), qf[1] * __uint_as_float(a.y));
+        w.y = narrow_bf16x2(qf[2] * __uint_as_float(a.z), qf[3] * __uint_as_float(a.w));
+        w.z = narrow_bf16x2(qf[4] * __uint_as_float(b.x), qf[5] * __uint_as_float(b.y));
+        w.w = narrow_bf16x2(qf[6] * __uint_as_float(b.z), qf[7] * __uint_as_float(b.w));
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(out + at));
+    }
+}
+
+}  // namespace equarx

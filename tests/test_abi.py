@@ -132,6 +132,21 @@ def test_validation_rejects_before_launch(lib):
     assert rv(table(A, OUT, A, A), 4, n, blk, 9, OUT, None) == B.STATUS_BAD_SHAPE
     assert rv(ok4, 4, n, 96, 0, OUT, None) == B.STATUS_BAD_BLOCK
     assert rv(ok4, 4, 0, blk, 1, None, None) == B.STATUS_OK
+    qs_, ds_, ss_, rs_ = (lib.equarx_quantize_strided, lib.equarx_dequantize_strided, lib.equarx_reduce_stage_strided,
+                          lib.equarx_reduce_quantized_strided)
+    ns = 1024 * 64
+    assert qs_(A, ns, 48, A, A, None) == B.STATUS_BAD_BLOCK and qs_(A, ns, 256, A, A, None) == B.STATUS_BAD_BLOCK
+    assert qs_(A, ns + 1024, 64, A, A, None) == B.STATUS_BAD_SHAPE and qs_(A, -ns, 64, A, A, None) == B.STATUS_BAD_SHAPE
+    assert qs_(None, ns, 64, A, A, None) == B.STATUS_NULL_POINTER and qs_(A, ns, 64, ODD, A, None) == B.STATUS_MISALIGNED
+    assert qs_(None, 0, 64, None, None, None) == B.STATUS_OK
+    assert ds_(A, None, ns, 64, A, None) == B.STATUS_NULL_POINTER and ds_(A, A, ns, 64, A + 2, None) == B.STATUS_MISALIGNED
+    assert ds_(A, A, ns // 2, 64, A, None) == B.STATUS_BAD_SHAPE
+    assert ss_(A, A, None, ns, 64, A, A, None) == B.STATUS_NULL_POINTER and ss_(A, A, A, ns, 7, A, A, None) == B.STATUS_BAD_BLOCK
+    assert rs_(ok4, 4, ns, 64, OUT, WS, 0, None) == B.STATUS_WORKSPACE_TOO_SMALL
+    assert rs_(ok4, 4, ns, 64, OUT, None, 1 << 30, None) == B.STATUS_NULL_POINTER
+    assert rs_(ok4, 0, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
+    assert rs_(table(A, OUT, A, A), 4, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
+    assert rs_(ok4, 4, ns, 64, OUT, WS + 8, 1 << 30, None) == B.STATUS_MISALIGNED
     qb = lib.equarx_quantize_batch
     xs, cs, ss = table(A, A + 0x1000), table(A + 0x2000, A + 0x3000), table(A + 0x4000, A + 0x5000)
     assert qb(xs, cs, ss, 65, n, blk, None) == B.STATUS_BAD_SHAPE

@@ -603,3 +603,78 @@ def test_graph_capture_and_replay(gpu, oracle):
         want = oracle.reduce_chain(host, B)
         assert (gpu.host_u16(out_a) == want).all(), rep
         assert (gpu.host_u16(out_b) == want).all(), rep
+
+
+# ----------------------------------------------------------------------------- the paper's strided block geometry
+
+@pytest.mark.parametrize("chunks", (32, 64, 128))
+def test_strided_parity(gpu, oracle, chunks):
+    ms = 1024 * chunks
+    for i, (n, kind) in enumerate([(ms, "normal"), (3 * ms, "lognormal"), (5 * ms, "student"), (2 * ms, "tiny"),
+                                   (2 * ms, "sparse"), (2 * ms, "huge")]):
+        x = gpu.bf16_of(_values(kind, n, 9000 + i))
+        y = gpu.bf16_of(_values(kind, n, 9100 + i))
+        ns = n // chunks
+        dx, dy = gpu.dev_bf16(x), gpu.dev_bf16(y)
+        c = torch.full((n,), 99, dtype=torch.int8, device="cuda")
+        s_ = torch.full((ns,), -7.0, dtype=torch.float32, device="cuda")
+        eq.equarx_quantize_strided(dx, chunks, c, s_)
+        c2, s2 = torch.full_like(c, 98), torch.full_like(s_, -3.0)
+        eq.equarx_reduce_stage_strided(c, s_, dy, chunks, c2, s2)
+        out = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
+        eq.equarx_dequantize_strided(c2, s2, chunks, out)
+        torch.cuda.synchronize()
+        oc, os_ = oracle.quantize_bf16_strided(x, chunks)
+        assert (c.cpu().numpy() == oc).all() and (s_.cpu().numpy().view(np.uint32) == os_.view(np.uint32)).all(), (n, kind)
+        oc2, os2 = oracle.hop_strided(oc, os_, y, chunks)
+        assert (c2.cpu().numpy() == oc2).all() and (s2.cpu().numpy().view(np.uint32) == os2.view(np.uint32)).all(), (n, kind)
+        assert (gpu.host_u16(out) == oracle.dequantize_bf16_strided(oc2, os2, chunks)).all()
+        # in place
+        eq.equarx_reduce_stage_strided(c, s_, dy, chunks, c, s_)
+        torch.cuda.synchronize()
+        assert torch.equal(c, c2) and torch.equal(s_, s2)
+
+
+@pytest.mark.parametrize("chunks,P", ((64, 8), (32, 3), (128, 1), (64, 16)))
+def test_strided_chain_parity(gpu, oracle, chunks, P):
+    n = 3 * 1024 * chunks
+    parts = [gpu.bf16_of(_values("lognormal", n, 9500 + p)) for p in range(P)]
+    dev = [gpu.dev_bf16(p) for p in parts]
+    out = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_quantized_strided(dev, chunks, out, eq.alloc_workspace(P, n, chunks))
+    torch.cuda.synchronize()
+    assert (gpu.host_u16(out) == oracle.reduce_chain_strided(parts, chunks)).all()
+
+
+def test_strided_full_size_sampled(gpu, oracle):
+    """27B-shaped size, block 64 as in the paper's Fig. 7: minishards are independent, so the oracle on a sample
+    of minishards must reproduce the GPU's output there bit for bit."""
+    w = wl.WORKLOADS["c3_gemma3_27b"]
+    chunks = 64
+    host = wl.make_partials(w)
+    dev = [p.reshape(-1).cuda() for p in host]
+    out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_quantized_strided(dev, chunks, out, eq.alloc_workspace(w.P, w.n, chunks))
+    torch.cuda.synchronize()
+    got = gpu.host_u16(out)
+    ms = 1024 * chunks
+    total = w.n // ms
+    pick = np.unique(np.concatenate([[0, total - 1], _rng(5).integers(0, total, 24)]))
+    idx = (pick[:, None] * ms + np.arange(ms)[None, :]).reshape(-1)
+    want = oracle.reduce_chain_strided([wl.as_u16(p)[idx] for p in host], chunks)
+    assert (got[idx] == want).all()
+
+
+def test_strided_bad_arguments(gpu):
+    x = torch.zeros(1024 * 64, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(1024 * 64, dtype=torch.int8, device="cuda")
+    s_ = torch.zeros(1024, dtype=torch.float32, device="cuda")
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_quantize_strided(x, 48, c, s_)
+    assert e.value.status == eq.STATUS_BAD_BLOCK
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_quantize_strided(x[:1024 * 32], 64, c, s_)
+    assert e.value.status == eq.STATUS_BAD_SHAPE
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_quantized_strided([x, x], 64, torch.empty_like(x), torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == eq.STATUS_WORKSPACE_TOO_SMALL
