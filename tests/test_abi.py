@@ -184,3 +184,15 @@ def test_missing_library_is_an_error(monkeypatch, tmp_path):
     monkeypatch.setattr(build, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.load()
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/equarx.h is a C header: a C99 translation unit that includes it and takes the address of every
+    declared function compiles with gcc (no C++, no HIP, no torch types in the signatures)."""
+    import subprocess
+    names = declared_functions()
+    src = tmp_path / "use_header.c"
+    body = "\n".join(f"    p[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
+    src.write_text(f'#include "equarx.h"\nvoid (*p[{len(names)}])(void);\nvoid take(void) {{\n{body}\n}}\n')
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-c", str(src), "-I", os.path.dirname(HEADER),
+                    "-o", str(tmp_path / "use_header.o")], check=True)
