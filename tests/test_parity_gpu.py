@@ -678,3 +678,42 @@ def test_strided_bad_arguments(gpu):
     with pytest.raises(eq.EquarxError) as e:
         eq.equarx_reduce_quantized_strided([x, x], 64, torch.empty_like(x), torch.empty(256, dtype=torch.uint8, device="cuda"))
     assert e.value.status == eq.STATUS_WORKSPACE_TOO_SMALL
+
+
+# ----------------------------------------------------------------------------- lengths beyond 32-bit indices
+
+def test_length_beyond_two_to_the_31(gpu, oracle):
+    """A tensor of more than 2^31 elements (4.3 GB of bf16): element indices need 64 bits in every kernel.
+    Blocks are independent, so blocks sampled at the start, on both sides of the 2^31 boundary and at the ragged
+    end are checked against the oracle bit for bit, for quantize, hop, dequantize and the single-launch chain."""
+    n, B = (1 << 31) + 2048 * 5 + 24, 256
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    x = torch.randn(n, generator=g, device="cuda", dtype=torch.bfloat16)
+    y = torch.randn(n, generator=g, device="cuda", dtype=torch.bfloat16)
+    nb = eq.num_blocks(n, B)
+    c = torch.empty(n, dtype=torch.int8, device="cuda")
+    s_ = torch.empty(nb, dtype=torch.float32, device="cuda")
+    c2 = torch.empty(n, dtype=torch.int8, device="cuda")
+    s2 = torch.empty(nb, dtype=torch.float32, device="cuda")
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_quantize(x, B, c, s_)
+    eq.equarx_reduce_stage(c, s_, y, B, c2, s2)
+    eq.equarx_dequantize(c2, s2, B, out)
+    out_f = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_fused([x, y], B, out_f)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out_f.view(torch.int16))
+
+    edge = (1 << 31) // B
+    blocks = np.unique(np.concatenate([np.arange(0, 4), np.arange(edge - 4, edge + 4), np.arange(nb - 6, nb),
+                                       _rng(3).integers(0, nb, 200)]))
+    for b in blocks:
+        lo, hi = int(b) * B, min(n, (int(b) + 1) * B)
+        xs = x[lo:hi].view(torch.int16).cpu().numpy().view(np.uint16)
+        ys = y[lo:hi].view(torch.int16).cpu().numpy().view(np.uint16)
+        oc, os_ = oracle.quantize_bf16(xs, B)
+        assert (c[lo:hi].cpu().numpy() == oc).all() and s_[b].item() == os_[0], b
+        oc2, os2 = oracle.hop(oc, os_, ys, B)
+        assert (c2[lo:hi].cpu().numpy() == oc2).all() and s2[b].item() == os2[0], b
+        assert (out[lo:hi].view(torch.int16).cpu().numpy().view(np.uint16) == oracle.dequantize_bf16(oc2, os2, B)).all(), b
