@@ -1,0 +1,87 @@
+"""Speed and error of every flavour of the quantized reduction on one workload (python -m paper_2506_17615_amd.report).
+
+The paper's Sec. 4.1 / Fig. 7 compares its flavours -- full-loop or semi-loop, reduce-scatter and/or all-gather
+quantized -- by speedup and by mean squared error against the unquantized bf16 AllReduce, on a (4096, 4096)
+N(0,1) tensor over 8 devices with block size 64.  This prints the same comparison for the entry points of this
+library on one MI355X: time per reduction (all partials resident in HBM) and error against the exact sum.
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+import time
+
+import torch
+
+from . import binding as eq
+from . import build
+from . import workloads as wl
+
+FIG7 = wl.Workload("fig7", P=8, rows=4096, hidden=4096, block=64, dist="normal", seed=1007,
+                   note="the tensor of the paper's speedup-vs-error experiment")
+
+
+def _time_us(fn, reps: int) -> float:
+    for _ in range(5):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / reps * 1e6
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="fig7", help="fig7 or an id of workloads.WORKLOADS")
+    ap.add_argument("--reps", type=int, default=50)
+    args = ap.parse_args()
+    build.ensure_built()
+    eq.load()
+    w = FIG7 if args.workload == "fig7" else wl.WORKLOADS[args.workload]
+    P, n, B = w.P, w.n, w.block
+    parts = [p.reshape(-1).cuda() for p in wl.make_partials(w)]
+    ref = torch.zeros(n, dtype=torch.float64, device="cuda")
+    for p in parts:
+        ref += p.double()
+    base = ref.float().to(torch.bfloat16).double()          # what an unquantized bf16 AllReduce returns
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    work = eq.alloc_workspace(P, n, B)
+    nb = eq.num_blocks(n, B)
+    qc = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(P - 1)]
+    qs = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(P - 1)]
+
+    def flat():
+        eq.equarx_quantize_batch(parts[1:], B, qc, qs)
+        eq.equarx_reduce_flat(parts[0], qc, qs, B, out)
+
+    rows = [
+        ("full-loop RS+AG, hop by hop (P+1 launches)", lambda: eq.equarx_reduce_quantized(parts, B, out, work)),
+        ("full-loop RS+AG, one launch", lambda: eq.equarx_reduce_fused(parts, B, out)),
+        ("full-loop RS only", lambda: eq.equarx_reduce_variant(parts, B, eq.AG_UNQUANTIZED, out)),
+        ("full-loop AG only", lambda: eq.equarx_reduce_variant(parts, B, eq.RS_UNQUANTIZED, out)),
+        ("semi-loop RS+AG", lambda: eq.equarx_reduce_variant(parts, B, eq.SEMI_LOOP, out)),
+        ("semi-loop RS only", lambda: eq.equarx_reduce_variant(parts, B, eq.SEMI_LOOP | eq.AG_UNQUANTIZED, out)),
+        ("full-loop RS+AG, ring order per shard", lambda: eq.equarx_reduce_variant(parts, B, eq.RING_ORDER, out)),
+        ("all-to-all: batched quantize + flat reduce", flat),
+    ]
+    if B in eq.STRIDED_CHUNKS and n % (1024 * B) == 0:
+        rows.append(("full-loop RS+AG, strided 8x128-chunk blocks, hop by hop",
+                     lambda: eq.equarx_reduce_quantized_strided(parts, B, out, work)))
+
+    print(f"workload {w.name}: P={P}, n={n} ({w.rows} x {w.hidden}), block {B}, {w.dist}; MI355X, one GPU")
+    print(f"{'flavour':58s} {'us':>8s} {'eff. input GB/s':>16s} {'MSE vs bf16 sum':>16s} {'rel-L2 vs exact':>16s}")
+    for name, fn in rows:
+        us = _time_us(fn, args.reps)
+        fn()
+        torch.cuda.synchronize()
+        got = out.double()
+        mse = float(((got - base) ** 2).mean())
+        rel = float((got - ref).norm() / ref.norm())
+        print(f"{name:58s} {us:8.1f} {2.0 * P * n / us / 1e3:16.0f} {mse:16.3e} {rel:16.4f}", flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
