@@ -272,9 +272,9 @@ inline unsigned strided_grid(int64_t n, int32_t chunks)
 
 #define EQUARX_DISPATCH_CHUNKS(chunks, CALL) \
     switch (chunks) {                        \
-        case 32: CALL(4); break;             \
-        case 64: CALL(8); break;             \
-        case 128: CALL(16); break;           \
+        case 32: CALL(32 / kChunkGroups); break;   \
+        case 64: CALL(64 / kChunkGroups); break;   \
+        case 128: CALL(128 / kChunkGroups); break; \
         default: break;                      \
     }
 
