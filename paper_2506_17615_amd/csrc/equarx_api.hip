@@ -94,8 +94,8 @@ void launch_dequantize(const int8_t *codes, const float *scales, int64_t n, uint
            blocks_of(n, B));
 }
 
-// Single-launch chain, measured on MI355X (27B-shaped size): 4 tiles per thread and one partial of look-ahead
-// is fastest (62.7 us); deeper look-ahead (2..8 partials in flight) was 5-12 % slower, 1024-thread groups too.
+// Single-launch chain, measured on MI355X (27B-shaped size): 4 tiles per thread is fastest (63 us; 1, 2, 6, 8
+// tiles and 512- or 1024-thread groups are 1-8 % slower).
 #ifndef EQUARX_TILES_CHAIN
 #define EQUARX_TILES_CHAIN 4
 #endif
