@@ -52,24 +52,39 @@ def read_traffic():
 
 
 def cpu_baseline(w, host_u16, budget_s: float):
-    """The oracle as it stands, timed on this machine's host cores on the same workload."""
+    """The oracle as it stands, timed on this machine's host cores on the same workload (all cores, then one)."""
+    import numpy as np
+
     from oracle import equarx_oracle as orc
     orc.build()
     threads = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16") or 16)))
-    orc.set_threads(threads)
-    times = []
-    t_end = time.perf_counter() + budget_s
-    while len(times) < 10 and (not times or time.perf_counter() + times[-1] < t_end):
-        t0 = time.perf_counter()
-        orc.reduce_chain(host_u16, w.block)
-        times.append(time.perf_counter() - t0)
-    best = statistics.median(times)
+
+    def timed(nthreads, budget, most):
+        orc.set_threads(nthreads)
+        times = []
+        t_end = time.perf_counter() + budget
+        while len(times) < most and (not times or time.perf_counter() + times[-1] < t_end):
+            t0 = time.perf_counter()
+            out = orc.reduce_chain(host_u16, w.block)
+            times.append(time.perf_counter() - t0)
+        return statistics.median(times), len(times), out
+
+    best, reps, out = timed(threads, 0.7 * budget_s, 10)
+    used = orc.get_threads()
+    one, reps1, _ = timed(1, 0.3 * budget_s, 3)
+    orc.set_threads(1)
+    ref = orc.exact_sum_f64(host_u16)
+    got = orc.bf16_to_f32(out).astype(np.float64)
+    rel = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
     return {
         "value": round(2.0 * w.P * w.n / best / 1e9, 4),
         "unit": "GB/s effective input",
-        "cores": orc.get_threads(),
+        "cores": used,
         "kind": "oracle",
-        "sample": f"whole workload ({w.P} x {w.n} bf16), median of {len(times)} full chains, {best * 1e3:.0f} ms each",
+        "sample": f"whole workload ({w.P} x {w.n} bf16), median of {reps} full chains, {best * 1e3:.0f} ms each",
+        "single_thread_value": round(2.0 * w.P * w.n / one / 1e9, 4),
+        "single_thread_sample": f"median of {reps1} full chains, {one * 1e3:.0f} ms each",
+        "rel_l2_vs_exact_sum": rel,
     }
 
 
@@ -80,6 +95,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c3_gemma3_27b")
     ap.add_argument("--block", type=int, default=0, help="override the workload's block size")
+    ap.add_argument("--rows", type=int, default=0,
+                    help="override the workload's row count (e.g. rows/8: the share of one GPU of an 8-GPU node)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing; 0 skips it")
     ap.add_argument("--schedule", choices=("hop", "fused"), default="hop",
                     help="hop: P+1 launches, the wire written and read back (default, the schedule a ring imposes); "
@@ -102,6 +119,8 @@ def main() -> int:
     w = wl.WORKLOADS[args.workload]
     if args.block:
         w = w.with_block(args.block)
+    if args.rows:
+        w = w.with_rows(args.rows)
     K, W = args.steps, args.warmup
     P, n, B = w.P, w.n, w.block
 
