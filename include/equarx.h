@@ -224,6 +224,8 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
  *   equarx_reduce_quantized_strided: the hop-by-hop chain (P+1 launches);
  *            workspace of equarx_workspace_bytes(P, n, chunks) bytes, 256-byte aligned.
  *   equarx_reduce_stage_strided: codes_out / scales_out may alias the inputs.
+ *   equarx_reduce_fused_strided: the same chain in one launch (running sums in
+ *            registers, no wire traffic, no workspace); same bits.
  */
 int equarx_quantize_strided(const void *x_bf16, int64_t n, int32_t chunks,
                             int8_t *codes, float *scales, void *stream);
@@ -234,6 +236,8 @@ int equarx_reduce_stage_strided(const int8_t *codes_in, const float *scales_in, 
                                 int8_t *codes_out, float *scales_out, void *stream);
 int equarx_reduce_quantized_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
                                     void *out_bf16, void *workspace, size_t workspace_bytes, void *stream);
+int equarx_reduce_fused_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
+                                void *out_bf16, void *stream);
 
 /* Bytes of workspace equarx_reduce_quantized needs (0 for invalid arguments). */
 size_t equarx_workspace_bytes(int32_t P, int64_t n, int32_t block);

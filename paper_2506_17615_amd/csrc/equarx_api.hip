@@ -629,6 +629,24 @@ int equarx_reduce_quantized_strided(const void *const *partials_bf16, int32_t P,
     return launch_status();
 }
 
+int equarx_reduce_fused_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks, void *out_bf16,
+                                void *stream)
+{
+    if (int st = check_strided(n, chunks)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
+    PartialTable tab;
+    if (int st = fill_table(partials_bf16, P, out_bf16, tab)) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+#define CALL(RR) launch(chain_strided_kernel<RR>, strided_grid(n, chunks), hs, tab, P, static_cast<uint16_t *>(out_bf16))
+    EQUARX_DISPATCH_CHUNKS(chunks, CALL)
+#undef CALL
+    return launch_status();
+}
+
 int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream)
 {
     if (bytes == 0) return EQUARX_OK;

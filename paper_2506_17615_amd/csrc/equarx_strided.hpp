@@ -190,6 +190,77 @@ __global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin
     }
 }
 
+// The whole full-loop chain (reduce-scatter and all-gather quantized) in one
+// launch, strided geometry: the running fp32 sums of a thread's chunks stay in
+// registers (8 * R floats), every hop costs one pass over a partial, one trip
+// through LDS and two barriers.  Same operations in the same order as the
+// hop-by-hop strided chain, hence the same bits.
+template <int R>
+__global__ __launch_bounds__(kThreads) void chain_strided_kernel(const PartialTable tab, int P,
+                                                                 uint16_t *__restrict__ out)
+{
+    __shared__ uint32_t red[kChunkGroups][kSlicePos];
+    constexpr int chunks = R * kChunkGroups;
+    const StridedSpot sp = strided_spot(chunks);
+
+    float t[R][8];
+    {
+        u32x4 xv[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            xv[r] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(tab.x[0] + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) widen_bf16x8(xv[r], t[r]);
+    }
+
+    for (int i = 1; i <= P; ++i) {
+        // what device i-1 sends (i < P), or what the all-gather carries (i == P): Q of the running sum
+        u32x4 xv[R];
+        if (i < P) {
+            const uint16_t *x = tab.x[i];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                xv[r] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(x + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+            }
+        }
+        uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < R; ++r) note_absmax(t[r], m);
+        across_chunks_max(m, red);
+        float scale[8], inv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) block_quotients(__uint_as_float(m[j]), scale[j], inv[j]);
+        if (i < P) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                float xf[8];
+                widen_bf16x8(xv[r], xf);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float q = __builtin_rintf(t[r][j] * inv[j]);      // the code, as a float
+                    t[r][j] = __builtin_fmaf(q, scale[j], xf[j]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                float d[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) d[j] = (__builtin_rintf(t[r][j] * inv[j]) + 0.0f) * scale[j];   // +0.0: see quantize_lane_f
+                u32x4 w;
+                w.x = narrow_bf16x2(d[0], d[1]);
+                w.y = narrow_bf16x2(d[2], d[3]);
+                w.z = narrow_bf16x2(d[4], d[5]);
+                w.w = narrow_bf16x2(d[6], d[7]);
+                __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(out + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+            }
+        }
+    }
+}
+
 // Dequantize in the strided geometry: element e uses scale (e / (1024*chunks)) * 1024 + e % 1024, so the 8
 // elements of a lane use 8 consecutive scales.  n is a multiple of 1024, hence of the 2048-element tile.
 template <int K>

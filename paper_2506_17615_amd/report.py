@@ -35,11 +35,14 @@ def _time_us(fn, reps: int) -> float:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="fig7", help="fig7 or an id of workloads.WORKLOADS")
+    ap.add_argument("--block", type=int, default=0, help="block size instead of the workload's own")
     ap.add_argument("--reps", type=int, default=50)
     args = ap.parse_args()
     build.ensure_built()
     eq.load()
     w = FIG7 if args.workload == "fig7" else wl.WORKLOADS[args.workload]
+    if args.block:
+        w = w.with_block(args.block)
     P, n, B = w.P, w.n, w.block
     parts = [p.reshape(-1).cuda() for p in wl.make_partials(w)]
     ref = torch.zeros(n, dtype=torch.float64, device="cuda")
@@ -69,6 +72,8 @@ def main() -> int:
     if B in eq.STRIDED_CHUNKS and n % (1024 * B) == 0:
         rows.append(("full-loop RS+AG, strided 8x128-chunk blocks, hop by hop",
                      lambda: eq.equarx_reduce_quantized_strided(parts, B, out, work)))
+        rows.append(("full-loop RS+AG, strided 8x128-chunk blocks, one launch",
+                     lambda: eq.equarx_reduce_fused_strided(parts, B, out)))
 
     print(f"workload {w.name}: P={P}, n={n} ({w.rows} x {w.hidden}), block {B}, {w.dist}; MI355X, one GPU")
     print(f"{'flavour':58s} {'us':>8s} {'eff. input GB/s':>16s} {'MSE vs bf16 sum':>16s} {'rel-L2 vs exact':>16s}")

@@ -147,6 +147,12 @@ def test_validation_rejects_before_launch(lib):
     assert rs_(ok4, 0, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(table(A, OUT, A, A), 4, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(ok4, 4, ns, 64, OUT, WS + 8, 1 << 30, None) == B.STATUS_MISALIGNED
+    fs_ = lib.equarx_reduce_fused_strided
+    assert fs_(ok4, 4, ns, 64, None, None) == B.STATUS_NULL_POINTER and fs_(ok4, 4, ns, 96, OUT, None) == B.STATUS_BAD_BLOCK
+    assert fs_(ok4, 4, ns + 8, 64, OUT, None) == B.STATUS_BAD_SHAPE and fs_(ok4, 65, ns, 64, OUT, None) == B.STATUS_BAD_SHAPE
+    assert fs_(table(A, A, ODD, A), 4, ns, 64, OUT, None) == B.STATUS_MISALIGNED
+    assert fs_(table(A, A, OUT, A), 4, ns, 64, OUT, None) == B.STATUS_BAD_SHAPE
+    assert fs_(None, 4, 0, 64, None, None) == B.STATUS_NULL_POINTER and fs_(ok4, 4, 0, 64, None, None) == B.STATUS_OK
     qb = lib.equarx_quantize_batch
     xs, cs, ss = table(A, A + 0x1000), table(A + 0x2000, A + 0x3000), table(A + 0x4000, A + 0x5000)
     assert qb(xs, cs, ss, 65, n, blk, None) == B.STATUS_BAD_SHAPE

@@ -642,8 +642,23 @@ def test_strided_chain_parity(gpu, oracle, chunks, P):
     dev = [gpu.dev_bf16(p) for p in parts]
     out = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
     eq.equarx_reduce_quantized_strided(dev, chunks, out, eq.alloc_workspace(P, n, chunks))
+    out_f = torch.full((n,), 3.0, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_fused_strided(dev, chunks, out_f)
     torch.cuda.synchronize()
-    assert (gpu.host_u16(out) == oracle.reduce_chain_strided(parts, chunks)).all()
+    want = oracle.reduce_chain_strided(parts, chunks)
+    assert (gpu.host_u16(out) == want).all()
+    assert (gpu.host_u16(out_f) == want).all()
+
+
+@pytest.mark.parametrize("chunks", (32, 64, 128))
+def test_strided_fused_value_kinds(gpu, oracle, chunks):
+    n = 2 * 1024 * chunks
+    for kind in ("tiny", "sparse", "huge", "student"):
+        parts = [gpu.bf16_of(_values(kind, n, 9700 + p)) for p in range(4)]
+        out = torch.full((n,), 3.0, dtype=torch.bfloat16, device="cuda")
+        eq.equarx_reduce_fused_strided([gpu.dev_bf16(p) for p in parts], chunks, out)
+        torch.cuda.synchronize()
+        assert (gpu.host_u16(out) == oracle.reduce_chain_strided(parts, chunks)).all(), kind
 
 
 def test_strided_full_size_sampled(gpu, oracle):
@@ -655,7 +670,10 @@ def test_strided_full_size_sampled(gpu, oracle):
     dev = [p.reshape(-1).cuda() for p in host]
     out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
     eq.equarx_reduce_quantized_strided(dev, chunks, out, eq.alloc_workspace(w.P, w.n, chunks))
+    out_f = torch.empty_like(out)
+    eq.equarx_reduce_fused_strided(dev, chunks, out_f)
     torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out_f.view(torch.int16))
     got = gpu.host_u16(out)
     ms = 1024 * chunks
     total = w.n // ms
