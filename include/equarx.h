@@ -128,6 +128,20 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
                             int8_t *wire_codes, float *wire_scales, void *stream);
 
 /*
+ * The same hop-by-hop chain with its two ends fused: the first launch
+ * quantizes partial 0 in registers and performs hop 1, the last launch performs
+ * hop P-1 and the quantize/dequantize pair of the quantized all-gather
+ * (Sec. 3.1, 3.4), so c_0 and c_(P-1) never reach memory: P-1 launches instead
+ * of P+1, P-2 wire buffers written and read instead of P.  Same operations in
+ * the same order, hence the same bits as equarx_reduce_quantized.  P <= 2 is a
+ * single launch and ignores the workspace (which may then be NULL).
+ *
+ * Arguments as for equarx_reduce_quantized, without the optional kept wire.
+ */
+int equarx_reduce_quantized_fused_ends(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
+                                       void *out_bf16, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The same adder chain (Sec. 3.3 full-loop, Sec. 3.4) in ONE launch.  Blocks
  * do not interact, so every workgroup runs all hops on its own tiles with the
  * running codes and scale in registers: same operations, same order, same

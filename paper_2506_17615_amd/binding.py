@@ -36,6 +36,7 @@ SIGNATURES = {
     "equarx_dequantize": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp]),
     "equarx_reduce_stage": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "equarx_reduce_quantized": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp, _vp, _vp]),
+    "equarx_reduce_quantized_fused_ends": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp]),
     "equarx_reduce_fused": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp, _vp]),
     "equarx_reduce_variant": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp]),
     "equarx_reduce_flat": (ctypes.c_int, [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp,
@@ -195,6 +196,23 @@ def equarx_reduce_quantized(partials, block: int, out_bf16, workspace=None, wire
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().equarx_reduce_quantized(table, P, n, block, _ptr(out_bf16), _ptr(workspace), ws_bytes,
                                           _ptr(wire_codes), _ptr(wire_scales), _stream()), "equarx_reduce_quantized")
+
+
+def equarx_reduce_quantized_fused_ends(partials, block: int, out_bf16, workspace=None) -> None:
+    """The hop-by-hop chain with its first two and last two passes fused (P-1 launches, same bits)."""
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+        if p.numel() != n:
+            raise ValueError("partials differ in length")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    if workspace is not None and not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace: need a contiguous CUDA tensor")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().equarx_reduce_quantized_fused_ends(table, P, n, block, _ptr(out_bf16), _ptr(workspace), ws_bytes,
+                                                     _stream()), "equarx_reduce_quantized_fused_ends")
 
 
 def equarx_reduce_fused(partials, block: int, out_bf16, wire_codes=None, wire_scales=None) -> None:

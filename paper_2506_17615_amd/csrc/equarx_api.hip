@@ -94,6 +94,28 @@ void launch_dequantize(const int8_t *codes, const float *scales, int64_t n, uint
            blocks_of(n, B));
 }
 
+template <int B>
+void launch_head(const uint16_t *x0, const uint16_t *x1, int64_t n, int8_t *cout, float *sout, hipStream_t s)
+{
+    launch(head_kernel<B, kTilesHop>, grid_for(n, kTilesHop), s, x0, x1, n, cout, sout, blocks_of(n, B));
+}
+
+template <int B>
+void launch_tail(const int8_t *cin, const float *sin, const uint16_t *x, int64_t n, uint16_t *out, hipStream_t s)
+{
+    launch(tail_kernel<B, kTilesHop>, grid_for(n, kTilesHop), s, cin, sin, x, n, out, blocks_of(n, B));
+}
+
+// P >= 3: [Q_B(x_0) + hop 1], hops 2 .. P-2, [hop P-1 + quantize/dequantize pair]; c_i lives in wire buffer i & 1.
+template <int B>
+void launch_fused_ends(const PartialTable &tab, int P, int64_t n, int8_t *const (&c)[2], float *const (&s)[2],
+                       uint16_t *out, hipStream_t hs)
+{
+    launch_head<B>(tab.x[0], tab.x[1], n, c[1], s[1], hs);
+    for (int i = 2; i + 1 < P; ++i) launch_hop<B>(c[(i - 1) & 1], s[(i - 1) & 1], tab.x[i], n, c[i & 1], s[i & 1], hs);
+    launch_tail<B>(c[(P - 2) & 1], s[(P - 2) & 1], tab.x[P - 1], n, out, hs);
+}
+
 // Single-launch chain, measured on MI355X (27B-shaped size): 4 tiles per thread is fastest (63 us; 1, 2, 6, 8
 // tiles and 512- or 1024-thread groups are 1-8 % slower).
 #ifndef EQUARX_TILES_CHAIN
@@ -476,6 +498,40 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
     return launch_status();
 }
 
+int equarx_reduce_quantized_fused_ends(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
+                                       void *out_bf16, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
+    PartialTable tab;
+    if (int st = fill_table(partials_bf16, P, out_bf16, tab)) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    uint16_t *out = static_cast<uint16_t *>(out_bf16);
+    if (P <= 2) {       // both ends meet: the chain is one launch and needs no wire
+#define CALL(BB) launch_chain<BB>(tab, P, n, true, true, false, out, nullptr, nullptr, 0, 0, hs)
+        EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+        return launch_status();
+    }
+    if (!workspace) return EQUARX_NULL_POINTER;
+    if (misaligned(workspace, kWorkspaceAlign)) return EQUARX_MISALIGNED;
+    if (workspace_bytes < equarx_workspace_bytes(P, n, block)) return EQUARX_WORKSPACE_TOO_SMALL;
+    const int64_t nb = blocks_of(n, block);
+    const size_t codes = round_up((size_t)n, kWorkspaceAlign);
+    const size_t scales = round_up((size_t)nb * sizeof(float), kWorkspaceAlign);
+    char *w = static_cast<char *>(workspace);
+    int8_t *const c[2] = {reinterpret_cast<int8_t *>(w), reinterpret_cast<int8_t *>(w + codes + scales)};
+    float *const s[2] = {reinterpret_cast<float *>(w + codes), reinterpret_cast<float *>(w + 2 * codes + scales)};
+#define CALL(BB) launch_fused_ends<BB>(tab, P, n, c, s, out, hs)
+    EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+    return launch_status();
+}
+
 int equarx_reduce_fused(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block, void *out_bf16,
                         int8_t *wire_codes, float *wire_scales, void *stream)
 {
@@ -618,8 +674,8 @@ int equarx_reduce_quantized_strided(const void *const *partials_bf16, int32_t P,
     const size_t codes = round_up((size_t)n, kWorkspaceAlign);
     const size_t scales = round_up((size_t)(n / chunks) * sizeof(float), kWorkspaceAlign);
     char *w = static_cast<char *>(workspace);
-    int8_t *c[2] = {reinterpret_cast<int8_t *>(w), reinterpret_cast<int8_t *>(w + codes + scales)};
-    float *s[2] = {reinterpret_cast<float *>(w + codes), reinterpret_cast<float *>(w + 2 * codes + scales)};
+    int8_t *const c[2] = {reinterpret_cast<int8_t *>(w), reinterpret_cast<int8_t *>(w + codes + scales)};
+    float *const s[2] = {reinterpret_cast<float *>(w + codes), reinterpret_cast<float *>(w + 2 * codes + scales)};
     hipStream_t hs = static_cast<hipStream_t>(stream);
     do_quantize_strided(partials_bf16[0], n, chunks, c[0], s[0], hs);
     for (int32_t i = 1; i < P; ++i) {

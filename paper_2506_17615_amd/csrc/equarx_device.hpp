@@ -527,6 +527,98 @@ __device__ __forceinline__ void finish_tile(const float (&t)[8], uint16_t *__res
     }
 }
 
+// ---------------------------------------------------------------- first and last launch of the end-fused schedule
+//
+// The hop-by-hop chain spends its first two launches on Q_B(x_0) and on hop 1,
+// and its last two on hop P-1 and on the dequantization.  On one device each
+// pair can share a launch: c_0 and c_(P-1) then stay in registers and 2 of the
+// P+1 passes (and 2 of the P wire round trips) disappear.  Same operations in
+// the same order, so the same bits.
+
+// (c_1, s_1) = Q_B( fma(codes_0, s_0, x_1) ),  (codes_0, s_0) = Q_B(x_0) kept in registers.
+template <int B, int K, bool kFull>
+__device__ __forceinline__ void head_body(const uint16_t *__restrict__ x0, const uint16_t *__restrict__ x1, int64_t n,
+                                          int8_t *__restrict__ cout, float *__restrict__ sout, int64_t nb,
+                                          int64_t wg_at)
+{
+    constexpr int G = B / kLaneElems;
+    const int lane_at = threadIdx.x * kLaneElems;
+    u32x4 av[K], bv[K];
+    load_tiles<K, kFull>(x0, wg_at, n, av);
+    load_tiles<K, kFull>(x1, wg_at, n, bv);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        float t[8], r[8], xf[8], s0;
+        widen_bf16x8(av[k], t);
+        quantize_lane_f<G, false>(t, r, s0);        // a -0.0 code only flips the sign of a zero sum, which Q_B ignores
+        widen_bf16x8(bv[k], xf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(r[j], s0, xf[j]);
+        float scale;
+        const u32x2 w = quantize_lane<G>(t, scale);
+        store_i8x8(cout, at, n, kFull, w);
+        const int64_t blk = at / B;
+        if ((threadIdx.x % G) == 0 && (kFull || blk < nb)) sout[blk] = scale;
+    }
+}
+
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void head_kernel(const uint16_t *__restrict__ x0,
+                                                        const uint16_t *__restrict__ x1, int64_t n,
+                                                        int8_t *__restrict__ cout, float *__restrict__ sout,
+                                                        int64_t nb)
+{
+    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
+    if (wg_at + kTileElems * K <= n) {
+        head_body<B, K, true>(x0, x1, n, cout, sout, nb, wg_at);
+    } else {
+        head_body<B, K, false>(x0, x1, n, cout, sout, nb, wg_at);
+    }
+}
+
+// out = bf16( DQ( Q_B( fma(codes_in, s_in, x) ) ) ): the last hop and the quantized all-gather's pair (Sec. 3.4).
+template <int B, int K, bool kFull>
+__device__ __forceinline__ void tail_body(const int8_t *__restrict__ cin, const float *__restrict__ sin,
+                                          const uint16_t *__restrict__ x, int64_t n, uint16_t *__restrict__ out,
+                                          int64_t nb, int64_t wg_at)
+{
+    const int lane_at = threadIdx.x * kLaneElems;
+    u32x4 xv[K];
+    u32x2 cv[K];
+    float sv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t at = wg_at + k * kTileElems + lane_at;
+        xv[k] = load_bf16x8(x, at, n, kFull);
+        cv[k] = load_i8x8(cin, at, n, kFull);
+        const int64_t blk = at / B;
+        sv[k] = (kFull || blk < nb) ? sin[blk] : 0.0f;
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        float xf[8], qf[8], t[8];
+        widen_bf16x8(xv[k], xf);
+        widen_i8x8(cv[k], qf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(qf[j], sv[k], xf[j]);
+        finish_tile<B, true, false, kFull>(t, out, nullptr, nullptr, 0, 0, 0, wg_at + k * kTileElems + lane_at, n);
+    }
+}
+
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void tail_kernel(const int8_t *__restrict__ cin, const float *__restrict__ sin,
+                                                        const uint16_t *__restrict__ x, int64_t n,
+                                                        uint16_t *__restrict__ out, int64_t nb)
+{
+    const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
+    if (wg_at + kTileElems * K <= n) {
+        tail_body<B, K, true>(cin, sin, x, n, out, nb, wg_at);
+    } else {
+        tail_body<B, K, false>(cin, sin, x, n, out, nb, wg_at);
+    }
+}
+
 // Position -> partial index on a ring of P devices, without a division: the
 // callers only ever step by one.
 __device__ __forceinline__ int ring_next(int j, int P) { return j + 1 == P ? 0 : j + 1; }

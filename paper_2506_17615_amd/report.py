@@ -61,6 +61,8 @@ def main() -> int:
 
     rows = [
         ("full-loop RS+AG, hop by hop (P+1 launches)", lambda: eq.equarx_reduce_quantized(parts, B, out, work)),
+        ("full-loop RS+AG, hop by hop, ends fused (P-1 launches)",
+         lambda: eq.equarx_reduce_quantized_fused_ends(parts, B, out, work)),
         ("full-loop RS+AG, one launch", lambda: eq.equarx_reduce_fused(parts, B, out)),
         ("full-loop RS only", lambda: eq.equarx_reduce_variant(parts, B, eq.AG_UNQUANTIZED, out)),
         ("full-loop AG only", lambda: eq.equarx_reduce_variant(parts, B, eq.RS_UNQUANTIZED, out)),

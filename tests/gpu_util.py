@@ -89,6 +89,16 @@ def gpu_chain_fused(partials_u16, B, keep_wire=True):
     return host_u16(out)
 
 
+def gpu_chain_fused_ends(partials_u16, B):
+    """Runs equarx_reduce_quantized_fused_ends (P-1 launches); returns the bf16 output bits."""
+    parts = [dev_bf16(p) for p in partials_u16]
+    P, n = len(parts), parts[0].numel()
+    out = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_quantized_fused_ends(parts, B, out, eq.alloc_workspace(P, n, B))
+    torch.cuda.synchronize()
+    return host_u16(out)
+
+
 def gpu_variant(partials_u16, B, flags):
     parts = [dev_bf16(p) for p in partials_u16]
     out = torch.full((parts[0].numel(),), 7.0, dtype=torch.bfloat16, device="cuda")

@@ -147,6 +147,16 @@ def test_validation_rejects_before_launch(lib):
     assert rs_(ok4, 0, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(table(A, OUT, A, A), 4, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(ok4, 4, ns, 64, OUT, WS + 8, 1 << 30, None) == B.STATUS_MISALIGNED
+    fe = lib.equarx_reduce_quantized_fused_ends
+    assert fe(ok4, 0, n, blk, OUT, WS, need, None) == B.STATUS_BAD_SHAPE and fe(ok4, 65, n, blk, OUT, WS, need, None) == B.STATUS_BAD_SHAPE
+    assert fe(None, 4, n, blk, OUT, WS, need, None) == B.STATUS_NULL_POINTER and fe(ok4, 4, n, blk, None, WS, need, None) == B.STATUS_NULL_POINTER
+    assert fe(ok4, 4, n, blk, OUT, None, need, None) == B.STATUS_NULL_POINTER
+    assert fe(ok4, 4, n, blk, OUT, WS, need - 1, None) == B.STATUS_WORKSPACE_TOO_SMALL
+    assert fe(ok4, 4, n, blk, OUT, WS + 16, need, None) == B.STATUS_MISALIGNED
+    assert fe(table(A, 0, A, A), 4, n, blk, OUT, WS, need, None) == B.STATUS_NULL_POINTER
+    assert fe(table(A, A, ODD, A), 4, n, blk, OUT, WS, need, None) == B.STATUS_MISALIGNED
+    assert fe(table(A, OUT, A, A), 4, n, blk, OUT, WS, need, None) == B.STATUS_BAD_SHAPE
+    assert fe(ok4, 4, n, 100, OUT, WS, need, None) == B.STATUS_BAD_BLOCK and fe(ok4, 4, 0, blk, None, None, 0, None) == B.STATUS_OK
     fs_ = lib.equarx_reduce_fused_strided
     assert fs_(ok4, 4, ns, 64, None, None) == B.STATUS_NULL_POINTER and fs_(ok4, 4, ns, 96, OUT, None) == B.STATUS_BAD_BLOCK
     assert fs_(ok4, 4, ns + 8, 64, OUT, None) == B.STATUS_BAD_SHAPE and fs_(ok4, 65, ns, 64, OUT, None) == B.STATUS_BAD_SHAPE

@@ -131,6 +131,8 @@ def _check_chain(gpu, oracle, parts, B):
     fout, fwc, fws = gpu.gpu_chain_fused(parts, B)
     assert (fout == oo).all() and (fwc == owc).all() and (fws.view(np.uint32) == ows.view(np.uint32)).all()
     assert (gpu.gpu_chain_fused(parts, B, keep_wire=False) == oo).all()
+    # hop by hop with both ends fused (P-1 launches)
+    assert (gpu.gpu_chain_fused_ends(parts, B) == oo).all()
 
 
 CHAIN_CASES = {
@@ -195,6 +197,7 @@ def test_empty_input_is_a_no_op(gpu):
     eq.equarx_reduce_stage(e8, e32, e16, 256, e8, e32)
     eq.equarx_reduce_quantized([e16, e16], 256, e16, None)
     eq.equarx_reduce_fused([e16, e16], 256, e16)
+    eq.equarx_reduce_quantized_fused_ends([e16, e16, e16], 256, e16, None)
     torch.cuda.synchronize()
 
 
@@ -265,6 +268,9 @@ def _sampled_blocks_check(gpu, oracle, w, n_sample=3000, seed=0):
     eq.equarx_reduce_fused(dev, B, out_f)
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int16), out_f.view(torch.int16))      # single-launch chain, every element
+    eq.equarx_reduce_quantized_fused_ends(dev, B, out_f, eq.alloc_workspace(P, n, B))
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out_f.view(torch.int16))      # ends fused, every element
     rc, rs = eq.wire_row_codes(n), eq.wire_row_scales(n, B)
     wc = torch.empty((P, rc), dtype=torch.int8, device="cuda")
     ws = torch.empty((P, rs), dtype=torch.float32, device="cuda")
