@@ -35,6 +35,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));   // one 8-byte acce
 #ifndef EQUARX_NT_STORE_BF16
 #define EQUARX_NT_STORE_BF16 1      // the bf16 output is not read again by this library
 #endif
+#ifndef EQUARX_SCHED_BARRIER
+#define EQUARX_SCHED_BARRIER 1      // keep every load of a thread ahead of its arithmetic
+#endif
 #ifndef EQUARX_NT_WIRE
 #define EQUARX_NT_WIRE 0            // the wire is re-read by the next hop: keep it cacheable
 #endif
@@ -188,6 +191,16 @@ __device__ __forceinline__ void store_bf16x8(uint16_t *p, int64_t at, int64_t n,
     }
 }
 
+// With all K tiles of a thread in one basic block the instruction scheduler
+// would sink some loads between the arithmetic of earlier tiles to save
+// registers; the kernels want every request in flight before the first wait.
+__device__ __forceinline__ void loads_first()
+{
+#if EQUARX_SCHED_BARRIER
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+}
+
 // ---------------------------------------------------------------- the two quotients of a block
 
 // 127 / a is taken through the hardware reciprocal below this bound; from 2^126
@@ -206,27 +219,27 @@ constexpr float kRcpSafeBelow = 8.507059173e37f;    // 2^126
 //   127 / a : q0 = 127*rcp(a), then the same correction with the 1-ulp
 //             hardware reciprocal.
 // That they equal the IEEE quotient is not argued but CHECKED, exhaustively,
-// over every fp32 a in [127*2^-126, 2^126) -- selftest_quotients_kernel below,
-// run by the GPU tests -- and above 2^126 the IEEE division itself is used.
+// over every finite fp32 a >= 127*2^-126 -- selftest_quotients_kernel below,
+// run by the GPU tests.
 __device__ __forceinline__ void block_quotients(float a, float &scale, float &inv)
 {
-    if (a < kTinyAbsmax) {
-        scale = 0.0f;
-        inv = 0.0f;
-        return;
-    }
+    // Straight-line code (selects, no branches): the K tiles of a thread then
+    // form one basic block and the compiler interleaves their dependent chains.
     const float c = 1.0f / 127.0f;                      // folded at compile time: fl32(1/127)
     const float q0 = a * c;
     const float e = __builtin_fmaf(-127.0f, q0, a);     // exact remainder a - 127*q0
-    scale = __builtin_fmaf(e, c, q0);
-    if (__builtin_expect(a < kRcpSafeBelow, 1)) {
-        const float y = __builtin_amdgcn_rcpf(a);
-        const float p0 = 127.0f * y;
-        const float r = __builtin_fmaf(-a, p0, 127.0f); // exact remainder 127 - a*p0
-        inv = __builtin_fmaf(r, y, p0);
-    } else {
-        inv = 127.0f / a;
-    }
+    const float s = __builtin_fmaf(e, c, q0);
+    // From 2^126 on, 1/a is subnormal: divide a/16 instead and scale the
+    // quotient by 1/16, both exact (127/a >= 127*2^-128 is still normal).
+    const float f = a < kRcpSafeBelow ? 1.0f : 0.0625f;
+    const float af = a * f;
+    const float y = __builtin_amdgcn_rcpf(af);
+    const float p0 = 127.0f * y;
+    const float r = __builtin_fmaf(-af, p0, 127.0f);    // exact remainder 127 - af*p0
+    const float v = __builtin_fmaf(r, y, p0) * f;
+    const bool tiny = a < kTinyAbsmax;                  // what the lanes computed above (inf, NaN) is dropped
+    scale = tiny ? 0.0f : s;
+    inv = tiny ? 0.0f : v;
 }
 
 // Reference form of the same two quotients: the compiler's IEEE division.
@@ -270,27 +283,74 @@ __device__ __forceinline__ void quantize_lane_f(const float (&t)[8], float (&r)[
     }
 }
 
-// The 8 float-valued codes of a lane as packed int8.
+// Adding 1.5 * 2^23 to a float p, |p| < 2^22, rounds p to the nearest integer
+// (ties to even, the sum's ulp being 1 and the constant even) and leaves that
+// integer, in two's complement, in the low mantissa bits of the sum: the int8
+// code of p is the sum's low byte.  Two instructions (multiply, add) where
+// round + convert + mask would be four.
+constexpr float kRoundMagic = 12582912.0f;
+
+// Byte 0 of each of four words, gathered into one word.
+__device__ __forceinline__ uint32_t gather_low_bytes(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3)
+{
+    // v_perm_b32: selector 0..3 = byte of the second operand, 4..7 = byte of the first, 0x0c = zero
+    const uint32_t lo = __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(b3, b2, 0x04000c0cu);
+    return lo | hi;
+}
+
+// The 8 float-valued codes of a lane (integers in [-127, 127]) as packed int8.
 __device__ __forceinline__ u32x2 pack_codes(const float (&r)[8])
 {
+    uint32_t b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(r[i] + kRoundMagic);     // exact: r[i] is an integer
     u32x2 w;
-    w.x = pack_i8x4((int)r[0], (int)r[1], (int)r[2], (int)r[3]);
-    w.y = pack_i8x4((int)r[4], (int)r[5], (int)r[6], (int)r[7]);
+    w.x = gather_low_bytes(b[0], b[1], b[2], b[3]);
+    w.y = gather_low_bytes(b[4], b[5], b[6], b[7]);
     return w;
 }
 
+// Q_B of the 8 values of a lane, as packed int8 codes (same codes as
+// quantize_lane_f followed by pack_codes).
 template <int G>
 __device__ __forceinline__ u32x2 quantize_lane(const float (&t)[8], float &scale)
 {
-    float r[8];
-    quantize_lane_f<G>(t, r, scale);
-    return pack_codes(r);
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m = __builtin_fmaxf(m, __builtin_fabsf(t[i]));
+    const float a = __uint_as_float(group_max_bits<G>(__float_as_uint(m)));
+    float inv;
+    block_quotients(a, scale, inv);
+    uint32_t b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b[i] = __float_as_uint(t[i] * inv + kRoundMagic);   // two roundings: product, then sum
+    u32x2 w;
+    w.x = gather_low_bytes(b[0], b[1], b[2], b[3]);
+    w.y = gather_low_bytes(b[4], b[5], b[6], b[7]);
+    return w;
 }
 
 // ---------------------------------------------------------------- kernels
 // Each kernel body exists twice: kFull = true for workgroups whose K tiles lie
 // entirely inside [0, n) (straight-line vector code), kFull = false for the one
 // workgroup that holds the ragged end (every access guarded).
+
+// The K scales a group leader holds, stored after all K tiles are computed: one
+// conditional region at the end instead of one per tile, so the tiles'
+// arithmetic stays in a single basic block.
+template <int B, int K, bool kFull>
+__device__ __forceinline__ void store_group_scales(float *scales, const float (&scale)[K], int64_t wg_at, int64_t nb)
+{
+    constexpr int G = B / kLaneElems;
+    if ((threadIdx.x % G) == 0) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int64_t blk = (wg_at + k * kTileElems + threadIdx.x * kLaneElems) / B;
+            if (kFull || blk < nb) scales[blk] = scale[k];
+        }
+    }
+}
 
 template <int B, int K, bool kFull>
 __device__ __forceinline__ void quantize_body(const uint16_t *__restrict__ x, int64_t n, int8_t *__restrict__ codes,
@@ -302,18 +362,18 @@ __device__ __forceinline__ void quantize_body(const uint16_t *__restrict__ x, in
     u32x4 xv[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) xv[k] = load_bf16x8(x, wg_at + k * kTileElems + lane_at, n, kFull);
+    loads_first();
 
+    float scale[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int64_t at = wg_at + k * kTileElems + lane_at;
         float t[8];
         widen_bf16x8(xv[k], t);
-        float scale;
-        const u32x2 w = quantize_lane<G>(t, scale);
+        const u32x2 w = quantize_lane<G>(t, scale[k]);
         store_i8x8(codes, at, n, kFull, w);
-        const int64_t blk = at / B;
-        if ((threadIdx.x % G) == 0 && (kFull || blk < nb)) scales[blk] = scale;
     }
+    store_group_scales<B, K, kFull>(scales, scale, wg_at, nb);
 }
 
 // Pass 0 of the chain: quantize a bf16 tensor.
@@ -373,7 +433,9 @@ __device__ __forceinline__ void hop_body(const int8_t *cin, const float *sin, co
         const int64_t blk = at / B;
         sv[k] = (kFull || blk < nb) ? sin[blk] : 0.0f;
     }
+    loads_first();
 
+    float scale[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int64_t at = wg_at + k * kTileElems + lane_at;
@@ -382,12 +444,10 @@ __device__ __forceinline__ void hop_body(const int8_t *cin, const float *sin, co
         widen_i8x8(cv[k], qf);
 #pragma unroll
         for (int i = 0; i < 8; ++i) t[i] = __builtin_fmaf(qf[i], sv[k], xf[i]);
-        float scale;
-        const u32x2 w = quantize_lane<G>(t, scale);
+        const u32x2 w = quantize_lane<G>(t, scale[k]);
         store_i8x8(cout, at, n, kFull, w);
-        const int64_t blk = at / B;
-        if ((threadIdx.x % G) == 0 && (kFull || blk < nb)) sout[blk] = scale;
     }
+    store_group_scales<B, K, kFull>(sout, scale, wg_at, nb);
 }
 
 // One hop: dequantize the incoming wire, add the local bf16 shard in fp32
@@ -546,6 +606,8 @@ __device__ __forceinline__ void head_body(const uint16_t *__restrict__ x0, const
     u32x4 av[K], bv[K];
     load_tiles<K, kFull>(x0, wg_at, n, av);
     load_tiles<K, kFull>(x1, wg_at, n, bv);
+    loads_first();
+    float scale[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int64_t at = wg_at + k * kTileElems + lane_at;
@@ -555,12 +617,10 @@ __device__ __forceinline__ void head_body(const uint16_t *__restrict__ x0, const
         widen_bf16x8(bv[k], xf);
 #pragma unroll
         for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(r[j], s0, xf[j]);
-        float scale;
-        const u32x2 w = quantize_lane<G>(t, scale);
+        const u32x2 w = quantize_lane<G>(t, scale[k]);
         store_i8x8(cout, at, n, kFull, w);
-        const int64_t blk = at / B;
-        if ((threadIdx.x % G) == 0 && (kFull || blk < nb)) sout[blk] = scale;
     }
+    store_group_scales<B, K, kFull>(sout, scale, wg_at, nb);
 }
 
 template <int B, int K>
@@ -595,6 +655,7 @@ __device__ __forceinline__ void tail_body(const int8_t *__restrict__ cin, const 
         const int64_t blk = at / B;
         sv[k] = (kFull || blk < nb) ? sin[blk] : 0.0f;
     }
+    loads_first();
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         float xf[8], qf[8], t[8];

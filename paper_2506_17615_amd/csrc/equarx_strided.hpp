@@ -80,10 +80,13 @@ __device__ __forceinline__ void note_absmax(const float (&t)[8], uint32_t (&m)[8
 
 __device__ __forceinline__ u32x2 scale_and_pack(const float (&t)[8], const float (&inv)[8])
 {
-    float r[8];
+    uint32_t b[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) r[j] = __builtin_rintf(t[j] * inv[j]);
-    return pack_codes(r);
+    for (int j = 0; j < 8; ++j) b[j] = __float_as_uint(t[j] * inv[j] + kRoundMagic);  // rounds to the integer code
+    u32x2 w;
+    w.x = gather_low_bytes(b[0], b[1], b[2], b[3]);
+    w.y = gather_low_bytes(b[4], b[5], b[6], b[7]);
+    return w;
 }
 
 // R = chunks / 8 chunks per thread.
