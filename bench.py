@@ -242,35 +242,47 @@ def main() -> int:
         max_abs = float(diff.abs().max())
         del ref, diff
 
-        # the same K steps, taken apart through the per-stage entry points, each hop launch carrying its own
-        # pair of HIP events: the dominant kernel's duration, launch by launch
+        # the same K steps once more, each call with a pair of HIP events recorded on the stream around its hops
+        # (launches 1..P-1 of the call): the dominant kernel's duration inside the real chain, back to back as it
+        # runs there, nothing attached to the kernels themselves
         codes = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(2)]
         scales = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(2)]
-        pairs = []
-        for _ in range(K * max(P - 1, 1)):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            b.record(stream)          # creates the underlying hipEvent_t handles
-            pairs.append((a, b))
-        torch.cuda.synchronize()
-        it = iter(pairs)
-        used = []
-        for k in range(K):
-            parts = sets[k % 2]
-            if P == 1:
-                a, b = next(it)
-                eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
-                used.append((a, b))
-            eq.equarx_quantize(parts[0], B, codes[0], scales[0])
-            for i in range(1, P):
-                a, b = next(it)
-                eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
-                used.append((a, b))
-                eq.equarx_reduce_stage(codes[(i - 1) & 1], scales[(i - 1) & 1], parts[i], B, codes[i & 1], scales[i & 1])
-            eq.equarx_dequantize(codes[(P - 1) & 1], scales[(P - 1) & 1], B, out)
-        torch.cuda.synchronize()
-        durs_ms = [a.elapsed_time(b) for a, b in used]
-        kernel_ms = statistics.fmean(durs_ms)
+
+        def event_pairs(count):
+            made = []
+            for _ in range(count):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                b.record(stream)          # creates the underlying hipEvent_t handles
+                made.append((a, b))
+            torch.cuda.synchronize()
+            return made
+
+        def per_launch_ms(call, first, count):
+            """Mean duration of one of `count` consecutive launches (from launch `first`) of call(k).  Spans of two
+            lengths are timed on alternate steps and subtracted, which cancels what the two event records cost."""
+            short = count // 2 if count >= 3 else 0
+            pairs = event_pairs(K)
+            for k, (a, b) in enumerate(pairs):
+                length = short if (short and k % 2) else count
+                eq.equarx_time_launch_span(first, first + length - 1, a.cuda_event, b.cuda_event)
+                call(k)
+            torch.cuda.synchronize()
+            times = [a.elapsed_time(b) for a, b in pairs]
+            if not short:
+                return statistics.fmean(times) / count, len(times) * count
+            long_ms, short_ms = statistics.fmean(times[0::2]), statistics.fmean(times[1::2])
+            return (long_ms - short_ms) / (count - short), len(times[0::2]) * count + len(times[1::2]) * short
+
+        kernel_ms, launches_timed = per_launch_ms(lambda k: eq.equarx_reduce_quantized(sets[k % 2], B, out, work),
+                                                  1 if P > 1 else 0, max(P - 1, 1))
+
+        # calibration: the hops' loads and stores without their arithmetic, same ping-pong, same cadence
+        traffic_only_ms = None
+        if P > 1 and n % B == 0:
+            traffic_only_ms, _ = per_launch_ms(
+                lambda k: eq.equarx_calib_hop_traffic(sets[k % 2], B, codes[0], scales[0], codes[1], scales[1]),
+                0, P - 1)
 
         # calibration: what a plain 16-byte copy reaches on this device over the same footprint
         src = torch.empty(2 * P * n // 2, dtype=torch.uint8, device="cuda")
@@ -324,7 +336,7 @@ def main() -> int:
         ms_per_step, chosen, other = fused_ms_per_step, fused_info, hop_info
         dominant = "chain (all hops in one launch)"
         per_launch = fused_bytes(P, n)
-        kernel_ms, durs_ms = fused_kernel_ms, fused_pairs
+        kernel_ms, launches_timed = fused_kernel_ms, len(fused_pairs)
         traffic = None
     achieved = per_launch / (kernel_ms * 1e-3) / 1e9
     value = 2.0 * P * n / (ms_per_step * 1e-3) / 1e9
@@ -349,7 +361,9 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": per_launch, "avg_launch_us": round(kernel_ms * 1e3, 3),
-                     "launches_timed": len(durs_ms), "copy_kernel_GBps": round(copy_gbps, 1)},
+                     "launches_timed": launches_timed, "copy_kernel_GBps": round(copy_gbps, 1),
+                     "same_traffic_no_arithmetic_us": (round(traffic_only_ms * 1e3, 3)
+                                                       if traffic_only_ms and args.schedule == "hop" else None)},
         "error_vs_exact_sum": {"rel_l2": rel_l2, "mse": mse, "max_abs": max_abs},
     }
     if args.cpu_seconds > 0:

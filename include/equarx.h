@@ -272,6 +272,19 @@ const char *equarx_status_string(int status);
  * find the HBM bandwidth a streaming kernel can reach on this device. */
 int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/* The chain's hops as memory traffic only: P-1 launches of a kernel with
+ * exactly the loads and stores of equarx_reduce_stage (same tiling, same
+ * access widths, the same ping-pong between two wire buffers, partial i read by
+ * launch i) whose only computation is an XOR -- the time the memory system
+ * alone needs for a hop, which the benchmark sets beside the hop kernel's.
+ * n must be a multiple of block.  (codes0, scales0) is the input of launch 1,
+ * which writes (codes1, scales1); launch 2 reads those and writes buffer 0,
+ * and so on.  Per launch and per 8 consecutive elements (the partial as four
+ * little-endian 32-bit words X0..X3, the codes read as two words C0, C1):
+ * codes written = (X0^X2^C0, X1^X3^C1); scales written = scales read. */
+int equarx_calib_hop_traffic(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
+                             int8_t *codes0, float *scales0, int8_t *codes1, float *scales1, void *stream);
+
 /*
  * Self-tests of the kernels' arithmetic (used by the test suite).
  *
@@ -299,6 +312,15 @@ int equarx_eval_quotients(const float *absmax, int64_t n, float *scale, float *i
  * hipEventElapsedTime(start, stop) is that one kernel's execution time.
  * The setting applies to exactly one launch; either handle may be NULL. */
 void equarx_time_next_launch(void *start_event, void *stop_event);
+
+/* Profiling aid for an entry point that launches several kernels.  Counting
+ * the calling thread's coming launches from 0, `start_event` is recorded on
+ * the launch's stream (hipEventRecord) just before launch `first` and
+ * `stop_event` just after launch `last` (last >= first >= 0): the elapsed time
+ * is that of launches first..last back to back, with nothing attached to the
+ * kernels themselves.  E.g. hops 1..P-1 of equarx_reduce_quantized are its
+ * launches 1..P-1.  One setting is pending at a time; invalid arguments cancel it. */
+void equarx_time_launch_span(int32_t first, int32_t last, void *start_event, void *stop_event);
 
 #ifdef __cplusplus
 }

@@ -51,6 +51,8 @@ SIGNATURES = {
     "equarx_wire_row_codes": (_i64, [_i64]),
     "equarx_wire_row_scales": (_i64, [_i64, _i32]),
     "equarx_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "equarx_calib_hop_traffic": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp]),
+    "equarx_time_launch_span": (None, [_i32, _i32, _vp, _vp]),
     "equarx_calib_copy": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
     "equarx_time_next_launch": (None, [_vp, _vp]),
     "equarx_selftest_quotients": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint64, _vp, _vp]),
@@ -342,6 +344,26 @@ def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
             and dst.numel() * dst.element_size() >= nbytes):
         raise ValueError("calib_copy: need contiguous CUDA tensors, dst at least as large as src")
     _check(load().equarx_calib_copy(_ptr(src), _ptr(dst), nbytes, _stream()), "equarx_calib_copy")
+
+
+def equarx_calib_hop_traffic(partials, block: int, codes0, scales0, codes1, scales1) -> None:
+    """The chain's P-1 hops as memory traffic only (XOR of what each launch read), ping-pong between two wires."""
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    nb = num_blocks(n, block) if block in BLOCK_SIZES else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+    for c, s in ((codes0, scales0), (codes1, scales1)):
+        _need(c, torch.int8, n, "codes")
+        _need(s, torch.float32, nb, "scales")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    _check(load().equarx_calib_hop_traffic(table, P, n, block, _ptr(codes0), _ptr(scales0), _ptr(codes1),
+                                           _ptr(scales1), _stream()), "equarx_calib_hop_traffic")
+
+
+def equarx_time_launch_span(first: int, last: int, start_event, stop_event) -> None:
+    """Raw hipEvent_t handles recorded before the thread's launch `first` and after its launch `last` (from 0)."""
+    load().equarx_time_launch_span(first, last, start_event, stop_event)
 
 
 def equarx_time_next_launch(start_event, stop_event) -> None:

@@ -68,13 +68,36 @@ inline int launch_status()
 thread_local hipEvent_t t_start_event = nullptr;
 thread_local hipEvent_t t_stop_event = nullptr;
 
+// Profiling aid (equarx_time_launch_span): plain events recorded on the stream
+// around a run of the calling thread's coming launches.
+thread_local hipEvent_t t_span_start = nullptr;
+thread_local hipEvent_t t_span_stop = nullptr;
+thread_local int t_span_first = 0;      // launches still to pass before the start event is recorded
+thread_local int t_span_last = 0;       // launches still to pass before the one the stop event follows
+
 template <typename... KArgs, typename... Args>
 inline void launch2d(void (*kernel)(KArgs...), unsigned grid_x, unsigned grid_y, hipStream_t s, Args... args)
 {
     hipEvent_t e0 = t_start_event, e1 = t_stop_event;
     t_start_event = nullptr;
     t_stop_event = nullptr;
+    if (t_span_start) {
+        if (t_span_first == 0) {
+            (void)hipEventRecord(t_span_start, s);
+            t_span_start = nullptr;
+        } else {
+            --t_span_first;
+        }
+    }
     hipExtLaunchKernelGGL(kernel, dim3(grid_x, grid_y), dim3(kThreads), 0, s, e0, e1, 0, static_cast<KArgs>(args)...);
+    if (t_span_stop) {
+        if (t_span_last == 0) {
+            (void)hipEventRecord(t_span_stop, s);
+            t_span_stop = nullptr;
+        } else {
+            --t_span_last;
+        }
+    }
 }
 
 template <typename... KArgs, typename... Args>
@@ -725,6 +748,35 @@ int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream)
     return launch_status();
 }
 
+int equarx_calib_hop_traffic(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block, int8_t *codes0,
+                             float *scales0, int8_t *codes1, float *scales1, void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (n % block != 0) return EQUARX_BAD_SHAPE;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!codes0 || !scales0 || !codes1 || !scales1) return EQUARX_NULL_POINTER;
+    if (misaligned(codes0, kAlign) || misaligned(scales0, kAlign) || misaligned(codes1, kAlign) ||
+        misaligned(scales1, kAlign))
+        return EQUARX_MISALIGNED;
+    if (codes0 == codes1 || scales0 == scales1) return EQUARX_BAD_SHAPE;
+    PartialTable tab;
+    if (int st = fill_table(partials_bf16, P, nullptr, tab)) return st;
+    const int64_t lanes = n / kLaneElems;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    u32x2 *c[2] = {reinterpret_cast<u32x2 *>(codes0), reinterpret_cast<u32x2 *>(codes1)};
+    float *s[2] = {scales0, scales1};
+#define CALL(BB)                                                                                      \
+    for (int32_t i = 1; i < P; ++i) {                                                                 \
+        launch(hop_traffic_kernel<BB, kTilesHop>, grid_for(n, kTilesHop), hs,                         \
+               reinterpret_cast<const u32x4 *>(tab.x[i]), c[(i - 1) & 1], s[(i - 1) & 1], lanes, c[i & 1], s[i & 1]); \
+    }
+    EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+    return launch_status();
+}
+
 int equarx_selftest_quotients(uint32_t first_bits, uint64_t count, uint64_t *mismatches, void *stream)
 {
     if (count == 0) return EQUARX_OK;
@@ -752,6 +804,19 @@ void equarx_time_next_launch(void *start_event, void *stop_event)
 {
     t_start_event = static_cast<hipEvent_t>(start_event);
     t_stop_event = static_cast<hipEvent_t>(stop_event);
+}
+
+void equarx_time_launch_span(int32_t first, int32_t last, void *start_event, void *stop_event)
+{
+    if (first < 0 || last < first || !start_event || !stop_event) {
+        t_span_start = nullptr;
+        t_span_stop = nullptr;
+        return;
+    }
+    t_span_first = first;
+    t_span_last = last;
+    t_span_start = static_cast<hipEvent_t>(start_event);
+    t_span_stop = static_cast<hipEvent_t>(stop_event);
 }
 
 }  // extern "C"

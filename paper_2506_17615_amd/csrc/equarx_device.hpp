@@ -1069,4 +1069,40 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const u32x4 *__restrict_
     }
 }
 
+// Calibration: the hop's memory traffic without its arithmetic.  Same loads
+// and stores per lane as hop_kernel (16 bytes of bf16, 8 bytes of codes, the
+// group's scale in; 8 bytes of codes and the group leader's scale out), the
+// same tiling; the "result" is an XOR of what was read.
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void hop_traffic_kernel(const u32x4 *__restrict__ x, const u32x2 *cin,
+                                                               const float *sin, int64_t lanes, u32x2 *cout,
+                                                               float *sout)
+{
+    constexpr int G = B / kLaneElems;
+    const int64_t at = (int64_t)blockIdx.x * (kThreads * K) + threadIdx.x;
+    u32x4 xv[K];
+    u32x2 cv[K];
+    float sv[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t i = at + k * kThreads;
+        if (i < lanes) {
+            xv[k] = __builtin_nontemporal_load(x + i);
+            cv[k] = cin[i];
+            sv[k] = sin[i / G];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int64_t i = at + k * kThreads;
+        if (i < lanes) {
+            u32x2 w;
+            w.x = xv[k].x ^ xv[k].z ^ cv[k].x;
+            w.y = xv[k].y ^ xv[k].w ^ cv[k].y;
+            cout[i] = w;
+            if ((threadIdx.x % G) == 0) sout[i / G] = sv[k];
+        }
+    }
+}
+
 }  // namespace equarx

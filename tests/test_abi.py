@@ -147,6 +147,17 @@ def test_validation_rejects_before_launch(lib):
     assert rs_(ok4, 0, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(table(A, OUT, A, A), 4, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(ok4, 4, ns, 64, OUT, WS + 8, 1 << 30, None) == B.STATUS_MISALIGNED
+    ht = lib.equarx_calib_hop_traffic
+    C0, C1 = A + 0x300000, A + 0x400000
+    assert ht(None, 4, n, blk, C0, C0 + 0x1000, C1, C1 + 0x1000, None) == B.STATUS_NULL_POINTER
+    assert ht(ok4, 4, n, blk, None, C0 + 0x1000, C1, C1 + 0x1000, None) == B.STATUS_NULL_POINTER
+    assert ht(ok4, 4, n + 8, blk, C0, C0 + 0x1000, C1, C1 + 0x1000, None) == B.STATUS_BAD_SHAPE
+    assert ht(ok4, 4, n, 100, C0, C0 + 0x1000, C1, C1 + 0x1000, None) == B.STATUS_BAD_BLOCK
+    assert ht(ok4, 65, n, blk, C0, C0 + 0x1000, C1, C1 + 0x1000, None) == B.STATUS_BAD_SHAPE
+    assert ht(ok4, 4, n, blk, ODD, C0 + 0x1000, C1, C1 + 0x1000, None) == B.STATUS_MISALIGNED
+    assert ht(ok4, 4, n, blk, C0, C0 + 0x1000, C0, C1 + 0x1000, None) == B.STATUS_BAD_SHAPE
+    assert ht(table(A, 0, A, A), 4, n, blk, C0, C0 + 0x1000, C1, C1 + 0x1000, None) == B.STATUS_NULL_POINTER
+    assert ht(ok4, 4, 0, blk, None, None, None, None, None) == B.STATUS_OK
     fe = lib.equarx_reduce_quantized_fused_ends
     assert fe(ok4, 0, n, blk, OUT, WS, need, None) == B.STATUS_BAD_SHAPE and fe(ok4, 65, n, blk, OUT, WS, need, None) == B.STATUS_BAD_SHAPE
     assert fe(None, 4, n, blk, OUT, WS, need, None) == B.STATUS_NULL_POINTER and fe(ok4, 4, n, blk, None, WS, need, None) == B.STATUS_NULL_POINTER

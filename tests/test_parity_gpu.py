@@ -248,6 +248,55 @@ def test_calibration_copy(gpu):
     assert torch.equal(src, dst)
 
 
+@pytest.mark.parametrize("B", (32, 256, 512))
+def test_calibration_hop_traffic(gpu, B):
+    """The memory-only stand-in for the chain's hops writes the documented XOR of what it read (so it really
+    reads all of it), launch after launch, ping-pong between the two wires."""
+    n = B * 4 * 53 + 2048 * 6          # several workgroups and a ragged last one
+    n -= n % B
+    rng = _rng(B)
+    P = 4
+    xs = [torch.from_numpy(rng.integers(0, 1 << 16, n, dtype=np.int64).astype(np.uint16).view(np.int16)).cuda()
+          .view(torch.bfloat16) for _ in range(P)]
+    c0 = torch.from_numpy(rng.integers(-128, 128, n, dtype=np.int64).astype(np.int8)).cuda()
+    s0 = torch.from_numpy(rng.standard_normal(n // B).astype(np.float32)).cuda()
+    c1, s1 = torch.zeros_like(c0), torch.zeros_like(s0)
+    cw = c0.cpu().numpy().view(np.uint32).reshape(-1, 2)
+    s_first = s0.clone()
+    eq.equarx_calib_hop_traffic(xs, B, c0, s0, c1, s1)
+    torch.cuda.synchronize()
+    for i in range(1, P):
+        xw = xs[i].view(torch.int16).cpu().numpy().view(np.uint32).reshape(-1, 4)
+        cw = np.stack([xw[:, 0] ^ xw[:, 2] ^ cw[:, 0], xw[:, 1] ^ xw[:, 3] ^ cw[:, 1]], axis=1)
+    last_c, last_s = (c1, s1) if (P - 1) & 1 else (c0, s0)
+    assert (last_c.cpu().numpy().view(np.uint32).reshape(-1, 2) == cw).all()
+    assert torch.equal(last_s, s_first)
+
+
+def test_time_launch_span_brackets_the_hops(gpu, oracle):
+    """Events recorded around launches 1..P-1 of a chain call give a plausible time, leave the result untouched,
+    and the setting is consumed by that call."""
+    w = wl.WORKLOADS["c1_small"]
+    parts = [p.reshape(-1).cuda() for p in wl.make_partials(w)]
+    out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+    work = eq.alloc_workspace(w.P, w.n, w.block)
+    want = oracle.reduce_chain([wl.as_u16(p) for p in wl.make_partials(w)], w.block)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    b.record()
+    torch.cuda.synchronize()
+    eq.equarx_time_launch_span(1, w.P - 1, a.cuda_event, b.cuda_event)
+    eq.equarx_reduce_quantized(parts, w.block, out, work)
+    torch.cuda.synchronize()
+    first = a.elapsed_time(b)
+    assert 0.0 < first < 2.0                                 # P-1 small kernels, in ms
+    assert (gpu.host_u16(out) == want).all()
+    eq.equarx_reduce_quantized(parts, w.block, out, work)    # nothing pending any more: the events stay as they are
+    torch.cuda.synchronize()
+    assert a.elapsed_time(b) == first
+    assert (gpu.host_u16(out) == want).all()
+
+
 # ----------------------------------------------------------------------------- full benchmark sizes
 
 def _sampled_blocks_check(gpu, oracle, w, n_sample=3000, seed=0):
