@@ -106,11 +106,6 @@ __device__ __forceinline__ void widen_i8x8(const u32x2 &w, float (&f)[8])
     }
 }
 
-__device__ __forceinline__ uint32_t pack_i8x4(int a, int b, int c, int d)
-{
-    return (uint32_t)(a & 0xFF) | ((uint32_t)(b & 0xFF) << 8) | ((uint32_t)(c & 0xFF) << 16) | ((uint32_t)d << 24);
-}
-
 __device__ __forceinline__ uint32_t narrow_bf16x2(float lo, float hi)
 {
     // gfx950 converts in hardware (round to nearest, ties to even)
@@ -203,8 +198,9 @@ __device__ __forceinline__ void loads_first()
 
 // ---------------------------------------------------------------- the two quotients of a block
 
-// 127 / a is taken through the hardware reciprocal below this bound; from 2^126
-// on, 1/a is subnormal and the reciprocal is no longer accurate enough.
+// 127 / a is taken through the hardware reciprocal of a below this bound; from
+// 2^126 on, 1/a is subnormal and the reciprocal is no longer accurate enough,
+// so a/16 is used there.
 constexpr float kRcpSafeBelow = 8.507059173e37f;    // 2^126
 
 // scale = fl32(a / 127) and inv = fl32(127 / a), both CORRECTLY ROUNDED, for a

@@ -223,3 +223,12 @@ def test_header_is_plain_c(tmp_path):
     src.write_text(f'#include "equarx.h"\nvoid (*p[{len(names)}])(void);\nvoid take(void) {{\n{body}\n}}\n')
     subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-c", str(src), "-I", os.path.dirname(HEADER),
                     "-o", str(tmp_path / "use_header.o")], check=True)
+
+
+def test_plain_c_client_builds_and_links():
+    """A C99 program that uses nothing but include/equarx.h and the HIP runtime's C API compiles and links against
+    the library (it runs in the GPU tests)."""
+    from tests import build_abi_client
+    binding.load()      # the library must be there to link against
+    path = build_abi_client.build(force=True)
+    assert os.path.exists(path) and os.access(path, os.X_OK)

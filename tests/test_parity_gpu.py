@@ -297,6 +297,22 @@ def test_time_launch_span_brackets_the_hops(gpu, oracle):
     assert (gpu.host_u16(out) == want).all()
 
 
+@pytest.mark.parametrize("P,n,B", ((4, 2048 * 5 + 300, 64), (8, 24 * 5376, 256)))
+def test_plain_c_client_drives_the_path(gpu, oracle, tmp_path, P, n, B):
+    """The C ABI without Python in between: a C99 program (tests/abi_client.c) allocates with the HIP runtime,
+    calls three schedules, checks they agree, and writes the result, which must be the oracle's bit for bit."""
+    import subprocess
+    from tests import build_abi_client
+    exe = build_abi_client.ensure_built()
+    parts = [gpu.bf16_of(_values("lognormal", n, 4100 + p)) for p in range(P)]
+    fin, fout = tmp_path / "in.bin", tmp_path / "out.bin"
+    np.concatenate(parts).astype("<u2").tofile(fin)
+    run = subprocess.run([exe, str(fin), str(fout), str(P), str(n), str(B)], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0, run.stdout + run.stderr
+    got = np.fromfile(fout, dtype="<u2")
+    assert (got == oracle.reduce_chain(parts, B)).all()
+
+
 # ----------------------------------------------------------------------------- full benchmark sizes
 
 def _sampled_blocks_check(gpu, oracle, w, n_sample=3000, seed=0):
