@@ -103,6 +103,46 @@ def test_hop_parity(gpu, oracle, B):
             assert (s.view(np.uint32) == so.view(np.uint32)).all(), (B, n, kind)
 
 
+@pytest.mark.parametrize("B", eq.BLOCK_SIZES)
+def test_quantize_and_hop_parity_near_the_largest_finite_values(gpu, oracle, B):
+    """Blocks whose max-abs lies in [2^126, 2^128): 1/absmax is subnormal there and the kernels take their
+    scaled-reciprocal route; codes and scales must still be the oracle's."""
+    n = 2048 * 4 + 5 * B + 24
+    rng = _rng(900 + B)
+    v = (rng.standard_normal(n) * 2.0 ** 100).astype(np.float32)
+    big = rng.random(n) < 0.02
+    v[big] = (rng.choice([-1.0, 1.0], big.sum()) * 2.0 ** (126 + 1.99 * rng.random(big.sum()))).astype(np.float32)
+    v[:B] = np.float32(2.0 ** 126)                     # exactly the boundary
+    v[B:2 * B] = np.float32(3.3895313892515355e38)     # the largest bf16
+    x = gpu.bf16_of(v)
+    c, s = gpu.gpu_quantize(x, B)
+    co, so = oracle.quantize_bf16(x, B)
+    assert (c == co).all() and (s.view(np.uint32) == so.view(np.uint32)).all()
+    assert np.isfinite(so).all() and (np.abs(co[:2 * B]) == 127).all()
+    zc = np.zeros(n, np.int8)
+    zs = np.ones(oracle.num_blocks(n, B), np.float32)
+    c2, s2 = gpu.gpu_hop(zc, zs, x, B)                 # 0 * 1 + x: the same values through the hop kernel
+    assert (c2 == co).all() and (s2.view(np.uint32) == so.view(np.uint32)).all()
+
+
+def test_random_shapes_and_values(gpu, oracle):
+    """Forty seeded draws of (P, n, block, value kind): ragged lengths at every alignment, through every
+    schedule of the chain (hop by hop with and without kept wire, ends fused, one launch)."""
+    rng = _rng(20250611)
+    for case in range(40):
+        P = int(rng.integers(1, 7))
+        B = int(rng.choice(eq.BLOCK_SIZES))
+        n = int(rng.integers(1, 3 * 2048 * 4 + 1)) if case % 4 else int(rng.integers(1, 600))
+        kind = KINDS[int(rng.integers(0, len(KINDS)))]
+        if kind == "huge":
+            kind = "student"       # sums of several huge values overflow; non-finite results are unspecified
+        parts = [gpu.bf16_of(_values(kind, n, 31000 + 10 * case + p)) for p in range(P)]
+        try:
+            _check_chain(gpu, oracle, parts, B)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: P={P} n={n} B={B} kind={kind}: {e}") from e
+
+
 def test_hop_in_place(gpu, oracle):
     for B in (32, 256, 512):
         n = 2048 * 7 + 640
