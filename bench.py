@@ -261,7 +261,7 @@ def main() -> int:
         def per_launch_ms(call, first, count):
             """Mean duration of one of `count` consecutive launches (from launch `first`) of call(k).  Spans of two
             lengths are timed on alternate steps and subtracted, which cancels what the two event records cost."""
-            short = count // 2 if count >= 3 else 0
+            short = count // 2 if count >= 3 and K >= 4 else 0
             pairs = event_pairs(K)
             for k, (a, b) in enumerate(pairs):
                 length = short if (short and k % 2) else count
