@@ -21,13 +21,14 @@ FIG7 = wl.Workload("fig7", P=8, rows=4096, hidden=4096, block=64, dist="normal",
                    note="the tensor of the paper's speedup-vs-error experiment")
 
 
-def _time_us(fn, reps: int) -> float:
-    for _ in range(5):
-        fn()
+def _time_us(fn, sets, reps: int) -> float:
+    """Wall clock per call, calls back to back, the resident input sets used in turn (as bench.py does)."""
+    for k in range(5):
+        fn(sets[k % len(sets)])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(reps):
-        fn()
+    for k in range(reps):
+        fn(sets[k % len(sets)])
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / reps * 1e6
 
@@ -45,6 +46,7 @@ def main() -> int:
         w = w.with_block(args.block)
     P, n, B = w.P, w.n, w.block
     parts = [p.reshape(-1).cuda() for p in wl.make_partials(w)]
+    sets = [parts, [p.clone() for p in parts]]      # two sets, together larger than the 256 MB Infinity Cache
     ref = torch.zeros(n, dtype=torch.float64, device="cuda")
     for p in parts:
         ref += p.double()
@@ -55,38 +57,44 @@ def main() -> int:
     qc = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(P - 1)]
     qs = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(P - 1)]
 
-    def flat():
-        eq.equarx_quantize_batch(parts[1:], B, qc, qs)
-        eq.equarx_reduce_flat(parts[0], qc, qs, B, out)
+    def flat(ps):
+        eq.equarx_quantize_batch(ps[1:], B, qc, qs)
+        eq.equarx_reduce_flat(ps[0], qc, qs, B, out)
+
+    wire_c = torch.empty((P, eq.wire_row_codes(n)), dtype=torch.int8, device="cuda")
+    wire_s = torch.empty((P, eq.wire_row_scales(n, B)), dtype=torch.float32, device="cuda")
 
     rows = [
-        ("full-loop RS+AG, hop by hop (P+1 launches)", lambda: eq.equarx_reduce_quantized(parts, B, out, work)),
+        ("full-loop RS+AG, hop by hop (P+1 launches)", lambda ps: eq.equarx_reduce_quantized(ps, B, out, work)),
         ("full-loop RS+AG, hop by hop, ends fused (P-1 launches)",
-         lambda: eq.equarx_reduce_quantized_fused_ends(parts, B, out, work)),
-        ("full-loop RS+AG, one launch", lambda: eq.equarx_reduce_fused(parts, B, out)),
-        ("full-loop RS only", lambda: eq.equarx_reduce_variant(parts, B, eq.AG_UNQUANTIZED, out)),
-        ("full-loop AG only", lambda: eq.equarx_reduce_variant(parts, B, eq.RS_UNQUANTIZED, out)),
-        ("semi-loop RS+AG", lambda: eq.equarx_reduce_variant(parts, B, eq.SEMI_LOOP, out)),
-        ("semi-loop RS only", lambda: eq.equarx_reduce_variant(parts, B, eq.SEMI_LOOP | eq.AG_UNQUANTIZED, out)),
-        ("full-loop RS+AG, ring order per shard", lambda: eq.equarx_reduce_variant(parts, B, eq.RING_ORDER, out)),
+         lambda ps: eq.equarx_reduce_quantized_fused_ends(ps, B, out, work)),
+        ("full-loop RS+AG, one launch", lambda ps: eq.equarx_reduce_fused(ps, B, out)),
+        ("full-loop RS+AG, one launch, every hop's wire written out",
+         lambda ps: eq.equarx_reduce_fused(ps, B, out, wire_c, wire_s)),
+        ("full-loop RS only", lambda ps: eq.equarx_reduce_variant(ps, B, eq.AG_UNQUANTIZED, out)),
+        ("full-loop AG only", lambda ps: eq.equarx_reduce_variant(ps, B, eq.RS_UNQUANTIZED, out)),
+        ("semi-loop RS+AG", lambda ps: eq.equarx_reduce_variant(ps, B, eq.SEMI_LOOP, out)),
+        ("semi-loop RS only", lambda ps: eq.equarx_reduce_variant(ps, B, eq.SEMI_LOOP | eq.AG_UNQUANTIZED, out)),
+        ("full-loop RS+AG, ring order per shard", lambda ps: eq.equarx_reduce_variant(ps, B, eq.RING_ORDER, out)),
         ("all-to-all: batched quantize + flat reduce", flat),
     ]
     if B in eq.STRIDED_CHUNKS and n % (1024 * B) == 0:
         rows.append(("full-loop RS+AG, strided 8x128-chunk blocks, hop by hop",
-                     lambda: eq.equarx_reduce_quantized_strided(parts, B, out, work)))
+                     lambda ps: eq.equarx_reduce_quantized_strided(ps, B, out, work)))
         rows.append(("full-loop RS+AG, strided 8x128-chunk blocks, one launch",
-                     lambda: eq.equarx_reduce_fused_strided(parts, B, out)))
+                     lambda ps: eq.equarx_reduce_fused_strided(ps, B, out)))
 
     print(f"workload {w.name}: P={P}, n={n} ({w.rows} x {w.hidden}), block {B}, {w.dist}; MI355X, one GPU")
     print(f"{'flavour':58s} {'us':>8s} {'eff. input GB/s':>16s} {'MSE vs bf16 sum':>16s} {'rel-L2 vs exact':>16s}")
-    for name, fn in rows:
-        us = _time_us(fn, args.reps)
-        fn()
-        torch.cuda.synchronize()
-        got = out.double()
-        mse = float(((got - base) ** 2).mean())
-        rel = float((got - ref).norm() / ref.norm())
-        print(f"{name:58s} {us:8.1f} {2.0 * P * n / us / 1e3:16.0f} {mse:16.3e} {rel:16.4f}", flush=True)
+    with torch.cuda.stream(torch.cuda.Stream()):
+        for name, fn in rows:
+            us = _time_us(fn, sets, args.reps)
+            fn(parts)
+            torch.cuda.synchronize()
+            got = out.double()
+            mse = float(((got - base) ** 2).mean())
+            rel = float((got - ref).norm() / ref.norm())
+            print(f"{name:58s} {us:8.1f} {2.0 * P * n / us / 1e3:16.0f} {mse:16.3e} {rel:16.4f}", flush=True)
     return 0
 
 
