@@ -690,6 +690,45 @@ def test_side_stream_and_repetition(gpu, oracle):
         assert (gpu.host_u16(out) == want).all()
 
 
+def test_two_host_threads_on_two_streams(gpu, oracle):
+    """The library keeps no shared state: two host threads, each with its own stream, inputs and workspace, call
+    it at the same time (ctypes releases the interpreter lock during a call) and both get the oracle's bits."""
+    import threading
+    cases = [CHAIN_CASES["c4"], CHAIN_CASES["c2_rows24"]]
+    hosts = [wl.make_partials(w) for w in cases]
+    wants = [oracle.reduce_chain([wl.as_u16(p) for p in h], w.block) for w, h in zip(cases, hosts)]
+    devs = [[p.reshape(-1).cuda() for p in h] for h in hosts]
+    works = [eq.alloc_workspace(w.P, w.n, w.block) for w in cases]
+    outs = [[torch.empty(w.n, dtype=torch.bfloat16, device="cuda") for _ in range(3)] for w in cases]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(i):
+        try:
+            w = cases[i]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for rep in range(30):
+                    eq.equarx_reduce_quantized(devs[i], w.block, outs[i][0], works[i])
+                    eq.equarx_reduce_fused(devs[i], w.block, outs[i][1])
+                    eq.equarx_reduce_quantized_fused_ends(devs[i], w.block, outs[i][2], works[i])
+            stream.synchronize()
+        except Exception as e:      # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not errors, errors
+    assert not any(t.is_alive() for t in threads)
+    torch.cuda.synchronize()
+    for i in range(2):
+        for o in outs[i]:
+            assert (gpu.host_u16(o) == wants[i]).all()
+
+
 def test_graph_capture_and_replay(gpu, oracle):
     """The entry points only enqueue kernels, so a caller may capture them in a HIP graph.  Replays are checked
     against the oracle after the inputs changed between replays."""
