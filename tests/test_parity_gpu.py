@@ -737,12 +737,17 @@ def test_graph_capture_and_replay(gpu, oracle):
     dev = [torch.zeros(n, dtype=torch.bfloat16, device="cuda") for _ in range(P)]
     out_a = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
     out_b = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    out_c = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    out_d = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
     work = eq.alloc_workspace(P, n, B)
+    work_c = eq.alloc_workspace(P, n, B)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         eq.equarx_reduce_quantized(dev, B, out_a, work)
         eq.equarx_reduce_fused(dev, B, out_b)
+        eq.equarx_reduce_quantized_fused_ends(dev, B, out_c, work_c)
+        eq.equarx_reduce_variant(dev, B, eq.SEMI_LOOP, out_d)
     for rep in range(3):
         host = [gpu.bf16_of(_values("lognormal", n, 6000 + 10 * rep + p)) for p in range(P)]
         for d, h in zip(dev, host):
@@ -753,6 +758,8 @@ def test_graph_capture_and_replay(gpu, oracle):
         want = oracle.reduce_chain(host, B)
         assert (gpu.host_u16(out_a) == want).all(), rep
         assert (gpu.host_u16(out_b) == want).all(), rep
+        assert (gpu.host_u16(out_c) == want).all(), rep
+        assert (gpu.host_u16(out_d) == oracle.reduce_semi_loop(host, B, True)).all(), rep
 
 
 # ----------------------------------------------------------------------------- the paper's strided block geometry
