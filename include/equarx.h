@@ -38,7 +38,7 @@ extern "C" {
 typedef enum equarx_status {
     EQUARX_OK = 0,
     EQUARX_NULL_POINTER = 1,        /* a required pointer is NULL */
-    EQUARX_BAD_SHAPE = 2,           /* n < 0, P < 1, P > EQUARX_MAX_PARTIALS, or aliasing that is not allowed */
+    EQUARX_BAD_SHAPE = 2,           /* n < 0, P < 1, P > EQUARX_MAX_PARTIALS, or overlap that is not allowed */
     EQUARX_BAD_BLOCK = 3,           /* block not in {32, 64, 128, 256, 512} */
     EQUARX_MISALIGNED = 4,          /* a data pointer is not 16-byte aligned */
     EQUARX_WORKSPACE_TOO_SMALL = 5, /* workspace_bytes < equarx_workspace_bytes(...) */
@@ -111,7 +111,12 @@ int equarx_reduce_stage(const int8_t *codes_in, const float *scales_in, const vo
  *
  *   partials_bf16   HOST array of P device pointers, each to n bf16 values,
  *                   in chain order; read before the call returns.
- *   out_bf16 [n]    device, must not alias a partial.
+ *   out_bf16 [n]    device.  May BE one of the partials (in-place reduction,
+ *                   as an AllReduce is usually called): every element of
+ *                   every partial is read before the output element is
+ *                   written.  An output that overlaps a partial without
+ *                   coinciding with it is rejected (EQUARX_BAD_SHAPE).  The
+ *                   same holds for every chain entry point below.
  *   workspace       device, at least equarx_workspace_bytes(P, n, block)
  *                   bytes, 256-byte aligned; holds the two ping-pong wire
  *                   buffers.  Not needed (may be NULL) when both wire_* are given.

@@ -270,16 +270,36 @@ void launch_flat(const uint16_t *local, const WireTable &tab, int R, int64_t n, 
     }
 }
 
-// Validates the P device pointers of a chain call and copies them into the kernel's table.
-inline int fill_table(const void *const *partials_bf16, int32_t P, const void *out_bf16, PartialTable &tab)
+// The output of a chain may BE one of the partials (in-place reduction: every
+// kernel reads an element of every partial before the thread that owns the
+// element writes it, and in the hop-by-hop schedules the output is written by
+// the last launch only).  An output that overlaps a partial without coinciding
+// with it would be read after it was overwritten.
+inline bool overlaps_without_coinciding(const void *partial, const void *out, int64_t n)
 {
-    for (int32_t i = 0; i < kMaxPartials; ++i) tab.x[i] = nullptr;
+    if (!out || partial == out) return false;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(partial), b = reinterpret_cast<uintptr_t>(out);
+    const uintptr_t bytes = (uintptr_t)n * sizeof(uint16_t);
+    return a < b + bytes && b < a + bytes;
+}
+
+// Validates the P device pointers of a chain call.
+inline int check_partials(const void *const *partials_bf16, int32_t P, int64_t n, const void *out_bf16)
+{
     for (int32_t i = 0; i < P; ++i) {
         if (!partials_bf16[i]) return EQUARX_NULL_POINTER;
         if (misaligned(partials_bf16[i], kAlign)) return EQUARX_MISALIGNED;
-        if (partials_bf16[i] == out_bf16) return EQUARX_BAD_SHAPE;
-        tab.x[i] = static_cast<const uint16_t *>(partials_bf16[i]);
+        if (overlaps_without_coinciding(partials_bf16[i], out_bf16, n)) return EQUARX_BAD_SHAPE;
     }
+    return EQUARX_OK;
+}
+
+// ... and copies them into the kernel's table.
+inline int fill_table(const void *const *partials_bf16, int32_t P, int64_t n, const void *out_bf16, PartialTable &tab)
+{
+    for (int32_t i = 0; i < kMaxPartials; ++i) tab.x[i] = nullptr;
+    if (int st = check_partials(partials_bf16, P, n, out_bf16)) return st;
+    for (int32_t i = 0; i < P; ++i) tab.x[i] = static_cast<const uint16_t *>(partials_bf16[i]);
     return EQUARX_OK;
 }
 
@@ -402,7 +422,7 @@ const char *equarx_status_string(int status)
     switch (status) {
         case EQUARX_OK: return "ok";
         case EQUARX_NULL_POINTER: return "a required pointer is NULL";
-        case EQUARX_BAD_SHAPE: return "bad shape: n < 0, P out of range, or forbidden aliasing";
+        case EQUARX_BAD_SHAPE: return "bad shape: n < 0, P out of range, or forbidden overlap of buffers";
         case EQUARX_BAD_BLOCK: return "block size must be 32, 64, 128, 256 or 512";
         case EQUARX_MISALIGNED: return "a data pointer is not 16-byte aligned";
         case EQUARX_WORKSPACE_TOO_SMALL: return "workspace is smaller than equarx_workspace_bytes()";
@@ -491,11 +511,7 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
     const bool keep_wire = wire_codes != nullptr;
     if (!keep_wire && !workspace) return EQUARX_NULL_POINTER;
     if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
-    for (int32_t i = 0; i < P; ++i) {
-        if (!partials_bf16[i]) return EQUARX_NULL_POINTER;
-        if (misaligned(partials_bf16[i], kAlign)) return EQUARX_MISALIGNED;
-        if (partials_bf16[i] == out_bf16) return EQUARX_BAD_SHAPE;
-    }
+    if (int st = check_partials(partials_bf16, P, n, out_bf16)) return st;
     const int64_t nb = blocks_of(n, block);
     int8_t *c[2];
     float *s[2];
@@ -545,7 +561,7 @@ int equarx_reduce_quantized_fused_ends(const void *const *partials_bf16, int32_t
     if (!out_bf16) return EQUARX_NULL_POINTER;
     if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
     PartialTable tab;
-    if (int st = fill_table(partials_bf16, P, out_bf16, tab)) return st;
+    if (int st = fill_table(partials_bf16, P, n, out_bf16, tab)) return st;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     uint16_t *out = static_cast<uint16_t *>(out_bf16);
     if (P <= 2) {       // both ends meet: the chain is one launch and needs no wire
@@ -581,7 +597,7 @@ int equarx_reduce_fused(const void *const *partials_bf16, int32_t P, int64_t n, 
     if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
     if (wire_codes && (misaligned(wire_codes, kAlign) || misaligned(wire_scales, kAlign))) return EQUARX_MISALIGNED;
     PartialTable tab;
-    if (int st = fill_table(partials_bf16, P, out_bf16, tab)) return st;
+    if (int st = fill_table(partials_bf16, P, n, out_bf16, tab)) return st;
     const int64_t c_step = equarx_wire_row_codes(n);
     const int64_t s_step = equarx_wire_row_scales(n, block);
     hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -609,7 +625,7 @@ int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n
     if (!out_bf16) return EQUARX_NULL_POINTER;
     if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
     PartialTable tab;
-    if (int st = fill_table(partials_bf16, P, out_bf16, tab)) return st;
+    if (int st = fill_table(partials_bf16, P, n, out_bf16, tab)) return st;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     uint16_t *out = static_cast<uint16_t *>(out_bf16);
     if (semi) {
@@ -701,11 +717,7 @@ int equarx_reduce_quantized_strided(const void *const *partials_bf16, int32_t P,
     if (n == 0) return EQUARX_OK;
     if (!out_bf16 || !workspace) return EQUARX_NULL_POINTER;
     if (misaligned(out_bf16, kAlign) || misaligned(workspace, kWorkspaceAlign)) return EQUARX_MISALIGNED;
-    for (int32_t i = 0; i < P; ++i) {
-        if (!partials_bf16[i]) return EQUARX_NULL_POINTER;
-        if (misaligned(partials_bf16[i], kAlign)) return EQUARX_MISALIGNED;
-        if (partials_bf16[i] == out_bf16) return EQUARX_BAD_SHAPE;
-    }
+    if (int st = check_partials(partials_bf16, P, n, out_bf16)) return st;
     // one scale per `chunks` elements: the same workspace as the contiguous chain with block = chunks
     if (workspace_bytes < equarx_workspace_bytes(P, n, chunks)) return EQUARX_WORKSPACE_TOO_SMALL;
     const size_t codes = round_up((size_t)n, kWorkspaceAlign);
@@ -732,7 +744,7 @@ int equarx_reduce_fused_strided(const void *const *partials_bf16, int32_t P, int
     if (!out_bf16) return EQUARX_NULL_POINTER;
     if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
     PartialTable tab;
-    if (int st = fill_table(partials_bf16, P, out_bf16, tab)) return st;
+    if (int st = fill_table(partials_bf16, P, n, out_bf16, tab)) return st;
     hipStream_t hs = static_cast<hipStream_t>(stream);
 #define CALL(RR) launch(chain_strided_kernel<RR>, strided_grid(n, chunks), hs, tab, P, static_cast<uint16_t *>(out_bf16))
     EQUARX_DISPATCH_CHUNKS(chunks, CALL)
@@ -767,7 +779,7 @@ int equarx_calib_hop_traffic(const void *const *partials_bf16, int32_t P, int64_
         return EQUARX_MISALIGNED;
     if (codes0 == codes1 || scales0 == scales1) return EQUARX_BAD_SHAPE;
     PartialTable tab;
-    if (int st = fill_table(partials_bf16, P, nullptr, tab)) return st;
+    if (int st = fill_table(partials_bf16, P, n, nullptr, tab)) return st;
     const int64_t lanes = n / kLaneElems;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     u32x2 *c[2] = {reinterpret_cast<u32x2 *>(codes0), reinterpret_cast<u32x2 *>(codes1)};

@@ -101,7 +101,7 @@ def test_validation_rejects_before_launch(lib):
     assert rq(ok4, 4, n, blk, OUT, WS + 16, need, None, None, None) == B.STATUS_MISALIGNED
     assert rq(table(A, 0, A, A), 4, n, blk, OUT, WS, need, None, None, None) == B.STATUS_NULL_POINTER
     assert rq(table(A, A, ODD, A), 4, n, blk, OUT, WS, need, None, None, None) == B.STATUS_MISALIGNED
-    assert rq(table(A, OUT, A, A), 4, n, blk, OUT, WS, need, None, None, None) == B.STATUS_BAD_SHAPE   # out aliases a partial
+    assert rq(table(A, OUT + 64, A, A), 4, n, blk, OUT, WS, need, None, None, None) == B.STATUS_BAD_SHAPE   # out overlaps a partial without being it
     assert rq(ok4, 4, n, blk, OUT, WS, need, A, None, None) == B.STATUS_NULL_POINTER                   # wire arrays come in pairs
     assert rq(ok4, 4, n, blk, OUT, None, 0, ODD, A, None) == B.STATUS_MISALIGNED
     assert rq(ok4, 4, n, 100, OUT, WS, need, None, None, None) == B.STATUS_BAD_BLOCK
@@ -116,7 +116,7 @@ def test_validation_rejects_before_launch(lib):
     assert rf(ok4, 4, n, blk, OUT, ODD, A, None) == B.STATUS_MISALIGNED
     assert rf(table(A, A, 0, A), 4, n, blk, OUT, None, None, None) == B.STATUS_NULL_POINTER
     assert rf(table(A, A, A, ODD), 4, n, blk, OUT, None, None, None) == B.STATUS_MISALIGNED
-    assert rf(table(OUT, A, A, A), 4, n, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE
+    assert rf(table(OUT - 2 * n + 16, A, A, A), 4, n, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE     # overlap
     assert rf(ok4, 4, n, 7, OUT, None, None, None) == B.STATUS_BAD_BLOCK
     assert rf(ok4, 4, -3, blk, OUT, None, None, None) == B.STATUS_BAD_SHAPE
     assert rf(ok4, 4, 0, blk, None, None, None, None) == B.STATUS_OK
@@ -129,7 +129,7 @@ def test_validation_rejects_before_launch(lib):
     assert rv(ok4, 4, n, blk, 8, None, None) == B.STATUS_NULL_POINTER
     assert rv(ok4, 4, n, blk, 1, OUT + 4, None) == B.STATUS_MISALIGNED
     assert rv(table(A, A, A, ODD), 4, n, blk, 4, OUT, None) == B.STATUS_MISALIGNED
-    assert rv(table(A, OUT, A, A), 4, n, blk, 9, OUT, None) == B.STATUS_BAD_SHAPE
+    assert rv(table(A, OUT + 16, A, A), 4, n, blk, 9, OUT, None) == B.STATUS_BAD_SHAPE
     assert rv(ok4, 4, n, 96, 0, OUT, None) == B.STATUS_BAD_BLOCK
     assert rv(ok4, 4, 0, blk, 1, None, None) == B.STATUS_OK
     qs_, ds_, ss_, rs_ = (lib.equarx_quantize_strided, lib.equarx_dequantize_strided, lib.equarx_reduce_stage_strided,
@@ -145,7 +145,7 @@ def test_validation_rejects_before_launch(lib):
     assert rs_(ok4, 4, ns, 64, OUT, WS, 0, None) == B.STATUS_WORKSPACE_TOO_SMALL
     assert rs_(ok4, 4, ns, 64, OUT, None, 1 << 30, None) == B.STATUS_NULL_POINTER
     assert rs_(ok4, 0, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
-    assert rs_(table(A, OUT, A, A), 4, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
+    assert rs_(table(A, OUT + 16, A, A), 4, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(ok4, 4, ns, 64, OUT, WS + 8, 1 << 30, None) == B.STATUS_MISALIGNED
     ht = lib.equarx_calib_hop_traffic
     C0, C1 = A + 0x300000, A + 0x400000
@@ -166,13 +166,13 @@ def test_validation_rejects_before_launch(lib):
     assert fe(ok4, 4, n, blk, OUT, WS + 16, need, None) == B.STATUS_MISALIGNED
     assert fe(table(A, 0, A, A), 4, n, blk, OUT, WS, need, None) == B.STATUS_NULL_POINTER
     assert fe(table(A, A, ODD, A), 4, n, blk, OUT, WS, need, None) == B.STATUS_MISALIGNED
-    assert fe(table(A, OUT, A, A), 4, n, blk, OUT, WS, need, None) == B.STATUS_BAD_SHAPE
+    assert fe(table(A, OUT + 16, A, A), 4, n, blk, OUT, WS, need, None) == B.STATUS_BAD_SHAPE
     assert fe(ok4, 4, n, 100, OUT, WS, need, None) == B.STATUS_BAD_BLOCK and fe(ok4, 4, 0, blk, None, None, 0, None) == B.STATUS_OK
     fs_ = lib.equarx_reduce_fused_strided
     assert fs_(ok4, 4, ns, 64, None, None) == B.STATUS_NULL_POINTER and fs_(ok4, 4, ns, 96, OUT, None) == B.STATUS_BAD_BLOCK
     assert fs_(ok4, 4, ns + 8, 64, OUT, None) == B.STATUS_BAD_SHAPE and fs_(ok4, 65, ns, 64, OUT, None) == B.STATUS_BAD_SHAPE
     assert fs_(table(A, A, ODD, A), 4, ns, 64, OUT, None) == B.STATUS_MISALIGNED
-    assert fs_(table(A, A, OUT, A), 4, ns, 64, OUT, None) == B.STATUS_BAD_SHAPE
+    assert fs_(table(A, A, OUT + 16, A), 4, ns, 64, OUT, None) == B.STATUS_BAD_SHAPE
     assert fs_(None, 4, 0, 64, None, None) == B.STATUS_NULL_POINTER and fs_(ok4, 4, 0, 64, None, None) == B.STATUS_OK
     qb = lib.equarx_quantize_batch
     xs, cs, ss = table(A, A + 0x1000), table(A + 0x2000, A + 0x3000), table(A + 0x4000, A + 0x5000)

@@ -268,11 +268,13 @@ def test_bad_arguments_raise(gpu):
     with pytest.raises(eq.EquarxError) as e:
         eq.equarx_quantize(x[1:], 256, c, s)
     assert e.value.status == eq.STATUS_MISALIGNED
+    big = torch.zeros(4096 + 8, dtype=torch.bfloat16, device="cuda")
+    shifted = big[8:]           # overlaps big[:4096] without being it (the output may BE a partial, see below)
     with pytest.raises(eq.EquarxError) as e:
-        eq.equarx_reduce_quantized([x, x], 256, x, eq.alloc_workspace(2, 4096, 256))
+        eq.equarx_reduce_quantized([x, big[:4096]], 256, shifted, eq.alloc_workspace(2, 4096, 256))
     assert e.value.status == eq.STATUS_BAD_SHAPE
     with pytest.raises(eq.EquarxError) as e:
-        eq.equarx_reduce_fused([x, x], 256, x)
+        eq.equarx_reduce_fused([big[:4096], x], 256, shifted)
     assert e.value.status == eq.STATUS_BAD_SHAPE
     small = torch.empty(256, dtype=torch.uint8, device="cuda")
     with pytest.raises(eq.EquarxError) as e:
@@ -688,6 +690,55 @@ def test_side_stream_and_repetition(gpu, oracle):
     side.synchronize()
     for out in outs:
         assert (gpu.host_u16(out) == want).all()
+
+
+@pytest.mark.parametrize("tiles", (3, 700, 2100))
+def test_in_place_output(gpu, oracle, tiles):
+    """The output may be one of the partials (an AllReduce is usually called in place): every schedule, each of
+    the single-launch kernel shapes (small / one tile per thread / several, paired), output = first, middle and
+    last partial."""
+    n, B, P = 2048 * tiles - 700, 128, 4
+    host = [gpu.bf16_of(_values("lognormal", n, 8100 + p)) for p in range(P)]
+    oracle.set_threads(8)
+    try:
+        want = oracle.reduce_chain(host, B)
+        want_semi = oracle.reduce_semi_loop(host, B, True)
+        want_ring = oracle.reduce_ring(host, B)
+    finally:
+        oracle.set_threads(1)
+    work = eq.alloc_workspace(P, n, B)
+    calls = {
+        "hop by hop": (lambda d, o: eq.equarx_reduce_quantized(d, B, o, work), want),
+        "ends fused": (lambda d, o: eq.equarx_reduce_quantized_fused_ends(d, B, o, work), want),
+        "one launch": (lambda d, o: eq.equarx_reduce_fused(d, B, o), want),
+        "semi-loop": (lambda d, o: eq.equarx_reduce_variant(d, B, eq.SEMI_LOOP, o), want_semi),
+        "ring order": (lambda d, o: eq.equarx_reduce_variant(d, B, eq.RING_ORDER, o), want_ring),
+    }
+    for name, (call, expect) in calls.items():
+        for j in (0, 1, P - 1):
+            dev = [gpu.dev_bf16(h) for h in host]
+            call(dev, dev[j])
+            torch.cuda.synchronize()
+            assert (gpu.host_u16(dev[j]) == expect).all(), (name, j)
+            for i in range(P):
+                if i != j:
+                    assert (gpu.host_u16(dev[i]) == host[i]).all(), (name, j, i)      # the others are untouched
+
+
+def test_in_place_output_strided(gpu, oracle):
+    chunks, P = 64, 3
+    n = 3 * 1024 * chunks
+    host = [gpu.bf16_of(_values("student", n, 8200 + p)) for p in range(P)]
+    want = oracle.reduce_chain_strided(host, chunks)
+    for fused in (False, True):
+        for j in range(P):
+            dev = [gpu.dev_bf16(h) for h in host]
+            if fused:
+                eq.equarx_reduce_fused_strided(dev, chunks, dev[j])
+            else:
+                eq.equarx_reduce_quantized_strided(dev, chunks, dev[j], eq.alloc_workspace(P, n, chunks))
+            torch.cuda.synchronize()
+            assert (gpu.host_u16(dev[j]) == want).all(), (fused, j)
 
 
 def test_two_host_threads_on_two_streams(gpu, oracle):
