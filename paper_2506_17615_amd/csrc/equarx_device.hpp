@@ -554,7 +554,7 @@ __device__ __forceinline__ void store_wire_tile(int8_t *__restrict__ wire_codes,
 
 // out = bf16(v) for the 8 fp32 values of one lane.
 template <bool kFull>
-__device__ __forceinline__ void store_narrowed_tile(uint16_t *__restrict__ out, int64_t at, int64_t n,
+__device__ __forceinline__ void store_narrowed_tile(uint16_t *out, int64_t at, int64_t n,
                                                     const float (&v)[8])
 {
     u32x4 w;
@@ -568,7 +568,7 @@ __device__ __forceinline__ void store_narrowed_tile(uint16_t *__restrict__ out, 
 // The last step of a chain for one tile: quantize the finished fp32 sum once
 // more and dequantize it (quantized all-gather, Sec. 3.4), or narrow it directly.
 template <int B, bool kAG, bool kWire, bool kFull>
-__device__ __forceinline__ void finish_tile(const float (&t)[8], uint16_t *__restrict__ out,
+__device__ __forceinline__ void finish_tile(const float (&t)[8], uint16_t *out,
                                             int8_t *__restrict__ wire_codes, float *__restrict__ wire_scales,
                                             int64_t c_step, int64_t s_step, int row, int64_t at, int64_t n)
 {
@@ -639,7 +639,7 @@ __global__ __launch_bounds__(kThreads) void head_kernel(const uint16_t *__restri
 // out = bf16( DQ( Q_B( fma(codes_in, s_in, x) ) ) ): the last hop and the quantized all-gather's pair (Sec. 3.4).
 template <int B, int K, bool kFull>
 __device__ __forceinline__ void tail_body(const int8_t *__restrict__ cin, const float *__restrict__ sin,
-                                          const uint16_t *__restrict__ x, int64_t n, uint16_t *__restrict__ out,
+                                          const uint16_t *x, int64_t n, uint16_t *out,
                                           int64_t nb, int64_t wg_at)
 {
     const int lane_at = threadIdx.x * kLaneElems;
@@ -668,8 +668,8 @@ __device__ __forceinline__ void tail_body(const int8_t *__restrict__ cin, const 
 
 template <int B, int K>
 __global__ __launch_bounds__(kThreads) void tail_kernel(const int8_t *__restrict__ cin, const float *__restrict__ sin,
-                                                        const uint16_t *__restrict__ x, int64_t n,
-                                                        uint16_t *__restrict__ out, int64_t nb)
+                                                        const uint16_t *x, int64_t n,      // out may be x (in place)
+                                                        uint16_t *out, int64_t nb)
 {
     const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
     if (wg_at + kTileElems * K <= n) {
@@ -732,7 +732,7 @@ __device__ __forceinline__ void hop_tiles(float (&t)[K][8], const u32x4 (&x)[K],
 // outstanding requests only lengthen its queues.
 template <int B, int K, bool kRS, bool kAG, bool kWire, bool kFull>
 __device__ __forceinline__ void chain_body(const PartialTable &tab, int P, int rot, int64_t n,
-                                           uint16_t *__restrict__ out, int8_t *__restrict__ wire_codes,
+                                           uint16_t *out, int8_t *__restrict__ wire_codes,
                                            float *__restrict__ wire_scales, int64_t c_step, int64_t s_step,
                                            int64_t wg_at)
 {
@@ -768,7 +768,7 @@ __device__ __forceinline__ void chain_body(const PartialTable &tab, int P, int r
 // same order: same bits.  Full tiles only; the kept-wire form stays on chain_body.
 template <int B, int K2, bool kRS, bool kAG>
 __device__ __forceinline__ void chain_body_paired(const PartialTable &tab, int P, int rot,
-                                                  uint16_t *__restrict__ out, int64_t wg_at)
+                                                  uint16_t *out, int64_t wg_at)
 {
     constexpr int Gh = B / 16;                      // lanes per block
     constexpr int kPairElems = 2 * kTileElems;      // 4096 elements per pair of pieces
@@ -884,7 +884,7 @@ __device__ __forceinline__ Span workgroup_span(int64_t n, int64_t shard_elems, i
 
 template <int B, int K, bool kRS, bool kAG, bool kWire>
 __global__ __launch_bounds__(kThreads) void chain_kernel(const PartialTable tab, int P, int64_t n, int64_t shard_elems,
-                                                         uint16_t *__restrict__ out, int8_t *__restrict__ wire_codes,
+                                                         uint16_t *out, int8_t *__restrict__ wire_codes,
                                                          float *__restrict__ wire_scales, int64_t c_step,
                                                          int64_t s_step)
 {
@@ -916,7 +916,7 @@ constexpr int kSmallBatch = 8;
 
 template <int B, bool kWire, bool kFull>
 __device__ __forceinline__ void chain_small_body(const PartialTable &tab, int P, int64_t n,
-                                                 uint16_t *__restrict__ out, int8_t *__restrict__ wire_codes,
+                                                 uint16_t *out, int8_t *__restrict__ wire_codes,
                                                  float *__restrict__ wire_scales, int64_t c_step, int64_t s_step,
                                                  int64_t wg_at)
 {
@@ -963,7 +963,7 @@ __device__ __forceinline__ void chain_small_body(const PartialTable &tab, int P,
 
 template <int B, bool kWire>
 __global__ __launch_bounds__(kThreads) void chain_small_kernel(const PartialTable tab, int P, int64_t n,
-                                                               uint16_t *__restrict__ out,
+                                                               uint16_t *out,
                                                                int8_t *__restrict__ wire_codes,
                                                                float *__restrict__ wire_scales, int64_t c_step,
                                                                int64_t s_step)
@@ -983,7 +983,7 @@ __global__ __launch_bounds__(kThreads) void chain_small_kernel(const PartialTabl
 // shorter counter-clockwise chain first.
 template <int B, int K, bool kAG, bool kFull>
 __device__ __forceinline__ void semi_body(const PartialTable &tab, int P, int rot, int64_t n,
-                                          uint16_t *__restrict__ out, int64_t wg_at)
+                                          uint16_t *out, int64_t wg_at)
 {
     const int lane_at = threadIdx.x * kLaneElems;
     const int h = P / 2;
@@ -1028,7 +1028,7 @@ __device__ __forceinline__ void semi_body(const PartialTable &tab, int P, int ro
 
 template <int B, int K, bool kAG>
 __global__ __launch_bounds__(kThreads) void semi_kernel(const PartialTable tab, int P, int64_t n, int64_t shard_elems,
-                                                        uint16_t *__restrict__ out)
+                                                        uint16_t *out)
 {
     const Span sp = workgroup_span<K>(n, shard_elems, 0);     // shard k: owner is device k
     if (!sp.any) return;

@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin
 // hop-by-hop strided chain, hence the same bits.
 template <int R>
 __global__ __launch_bounds__(kThreads) void chain_strided_kernel(const PartialTable tab, int P,
-                                                                 uint16_t *__restrict__ out)
+                                                                 uint16_t *out)
 {
     __shared__ uint32_t red[kChunkGroups][kSlicePos];
     constexpr int chunks = R * kChunkGroups;
