@@ -126,19 +126,22 @@ def test_quantize_and_hop_parity_near_the_largest_finite_values(gpu, oracle, B):
 
 
 def test_random_shapes_and_values(gpu, oracle):
-    """Forty seeded draws of (P, n, block, value kind): ragged lengths at every alignment, through every
-    schedule of the chain (hop by hop with and without kept wire, ends fused, one launch)."""
+    """Three hundred seeded draws of (P, n, block, value kind): ragged lengths at every alignment, through every
+    schedule of the chain (hop by hop with and without kept wire, ends fused, one launch) and one variant each."""
     rng = _rng(20250611)
-    for case in range(40):
-        P = int(rng.integers(1, 7))
+    variants = (eq.SEMI_LOOP, eq.AG_UNQUANTIZED, eq.RS_UNQUANTIZED, eq.RING_ORDER, eq.SEMI_LOOP | eq.AG_UNQUANTIZED)
+    for case in range(300):
+        P = int(rng.integers(1, 9))
         B = int(rng.choice(eq.BLOCK_SIZES))
         n = int(rng.integers(1, 3 * 2048 * 4 + 1)) if case % 4 else int(rng.integers(1, 600))
         kind = KINDS[int(rng.integers(0, len(KINDS)))]
         if kind == "huge":
             kind = "student"       # sums of several huge values overflow; non-finite results are unspecified
         parts = [gpu.bf16_of(_values(kind, n, 31000 + 10 * case + p)) for p in range(P)]
+        flags = int(variants[case % len(variants)])
         try:
             _check_chain(gpu, oracle, parts, B)
+            assert (gpu.gpu_variant(parts, B, flags) == _oracle_variant(oracle, parts, B, flags)).all(), flags
         except AssertionError as e:
             raise AssertionError(f"case {case}: P={P} n={n} B={B} kind={kind}: {e}") from e
 
