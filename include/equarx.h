@@ -309,6 +309,14 @@ int equarx_calib_hop_traffic(const void *const *partials_bf16, int32_t P, int64_
  * its own division.
  */
 int equarx_selftest_quotients(uint32_t first_bits, uint64_t count, uint64_t *mismatches, void *stream);
+
+/* The kernels take the int8 code of a scaled value p (|p| <= 127 up to
+ * rounding) from the low byte of fl32(p + 1.5 * 2^23) instead of rounding,
+ * converting and masking.  This compares the two, for +p and -p, over `count`
+ * consecutive fp32 bit patterns of |p| from first_bits (first_bits + count <=
+ * 0x43000000, i.e. |p| < 128) and adds the number of differences to
+ * mismatches[0] (device pointer, one uint64, zeroed by the caller). */
+int equarx_selftest_rounding(uint32_t first_bits, uint64_t count, uint64_t *mismatches, void *stream);
 int equarx_eval_quotients(const float *absmax, int64_t n, float *scale, float *inv, void *stream);
 
 /* Profiling aid.  The next kernel the calling thread launches through this

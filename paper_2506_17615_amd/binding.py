@@ -56,6 +56,7 @@ SIGNATURES = {
     "equarx_calib_copy": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
     "equarx_time_next_launch": (None, [_vp, _vp]),
     "equarx_selftest_quotients": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint64, _vp, _vp]),
+    "equarx_selftest_rounding": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint64, _vp, _vp]),
     "equarx_eval_quotients": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp]),
 }
 
@@ -375,6 +376,12 @@ def equarx_selftest_quotients(first_bits: int, count: int, mismatches: torch.Ten
     """mismatches: CUDA int64[2], zeroed by the caller; receives the counts of differing scales / reciprocals."""
     _need(mismatches, torch.int64, 2, "mismatches")
     _check(load().equarx_selftest_quotients(first_bits, count, _ptr(mismatches), _stream()), "equarx_selftest_quotients")
+
+
+def equarx_selftest_rounding(first_bits: int, count: int, mismatches: torch.Tensor) -> None:
+    """mismatches: CUDA int64[1], zeroed by the caller; receives the number of |p| patterns whose codes differ."""
+    _need(mismatches, torch.int64, 1, "mismatches")
+    _check(load().equarx_selftest_rounding(first_bits, count, _ptr(mismatches), _stream()), "equarx_selftest_rounding")
 
 
 def equarx_eval_quotients(absmax: torch.Tensor, scale: torch.Tensor, inv: torch.Tensor) -> None:

@@ -806,6 +806,18 @@ int equarx_selftest_quotients(uint32_t first_bits, uint64_t count, uint64_t *mis
     return launch_status();
 }
 
+int equarx_selftest_rounding(uint32_t first_bits, uint64_t count, uint64_t *mismatches, void *stream)
+{
+    if (count == 0) return EQUARX_OK;
+    if (!mismatches) return EQUARX_NULL_POINTER;
+    if (misaligned(mismatches, 8)) return EQUARX_MISALIGNED;
+    if ((uint64_t)first_bits + count > 0x43000000ull) return EQUARX_BAD_SHAPE;     // |p| < 128 only
+    const uint64_t wgs = (count + kThreads - 1) / kThreads;
+    launch(selftest_rounding_kernel, (unsigned)(wgs < 16384 ? wgs : 16384), static_cast<hipStream_t>(stream),
+           first_bits, count, reinterpret_cast<unsigned long long *>(mismatches));
+    return launch_status();
+}
+
 int equarx_eval_quotients(const float *absmax, int64_t n, float *scale, float *inv, void *stream)
 {
     if (n < 0 || n > ((int64_t)1 << 31)) return EQUARX_BAD_SHAPE;

@@ -1140,6 +1140,27 @@ __global__ __launch_bounds__(kThreads) void selftest_quotients_kernel(uint32_t f
     if (bad_inv) atomicAdd(&mismatches[1], (unsigned long long)bad_inv);
 }
 
+// Compares the code the kernels take from the low byte of p + 1.5 * 2^23 with
+// (int8) rint(p), for +p and -p, over `count` consecutive fp32 bit patterns of
+// |p| starting at first_bits (grid-stride).  mismatches[0] counts differences.
+__global__ __launch_bounds__(kThreads) void selftest_rounding_kernel(uint32_t first_bits, uint64_t count,
+                                                                      unsigned long long *mismatches)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    unsigned bad = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const float mag = __uint_as_float(first_bits + (uint32_t)i);
+#pragma unroll
+        for (int sign = 0; sign < 2; ++sign) {
+            const float p = sign ? -mag : mag;
+            const uint32_t fast = __float_as_uint(p + kRoundMagic) & 0xFFu;
+            const uint32_t plain = (uint32_t)(int)__builtin_rintf(p) & 0xFFu;
+            bad += fast != plain;
+        }
+    }
+    if (bad) atomicAdd(&mismatches[0], (unsigned long long)bad);
+}
+
 // Evaluates block_quotients on caller-chosen values, for comparison with a
 // division done on the host.
 __global__ __launch_bounds__(kThreads) void eval_quotients_kernel(const float *__restrict__ a, int64_t n,

@@ -147,6 +147,9 @@ def test_validation_rejects_before_launch(lib):
     assert rs_(ok4, 0, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(table(A, OUT + 16, A, A), 4, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(ok4, 4, ns, 64, OUT, WS + 8, 1 << 30, None) == B.STATUS_MISALIGNED
+    sr = lib.equarx_selftest_rounding
+    assert sr(0, 16, None, None) == B.STATUS_NULL_POINTER and sr(0, 16, A + 4, None) == B.STATUS_MISALIGNED
+    assert sr(0x42FFFFFF, 2, A, None) == B.STATUS_BAD_SHAPE and sr(0, 0, None, None) == B.STATUS_OK
     ht = lib.equarx_calib_hop_traffic
     C0, C1 = A + 0x300000, A + 0x400000
     assert ht(None, 4, n, blk, C0, C0 + 0x1000, C1, C1 + 0x1000, None) == B.STATUS_NULL_POINTER

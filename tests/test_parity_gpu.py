@@ -461,6 +461,20 @@ def test_block_quotients_equal_ieee_division_for_every_fp32(gpu):
     assert bad.tolist() == [0, 0]
 
 
+def test_codes_from_the_magic_number_add_equal_rint_for_every_fp32(gpu):
+    """The low byte of fl32(p + 1.5 * 2^23) is the int8 code (int8) rint(p) for EVERY fp32 p with |p| < 128,
+    both signs (the quantizer's scaled values lie in [-127, 127] up to rounding)."""
+    bad = torch.zeros(1, dtype=torch.int64, device="cuda")
+    hi = 0x43000000                    # 128.0f
+    step = 1 << 28
+    for first in range(0, hi, step):
+        eq.equarx_selftest_rounding(first, min(step, hi - first), bad)
+    torch.cuda.synchronize()
+    assert bad.tolist() == [0]
+    with pytest.raises(eq.EquarxError):
+        eq.equarx_selftest_rounding(hi - 1, 2, bad)       # beyond |p| < 128
+
+
 def test_block_quotients_equal_host_division(gpu):
     """... and the host's IEEE division (numpy fp32) on random patterns, every bf16 value and the range edges."""
     rng = _rng(77)
