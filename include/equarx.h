@@ -200,6 +200,32 @@ int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n
                           void *out_bf16, void *stream);
 
 /*
+ * Variants of the chain in the schedule a ring imposes: one launch per hop,
+ * every hop's wire written to memory once and read once (the single-launch
+ * forms above keep it in registers).  Same bits as equarx_reduce_variant with
+ * the same flags.
+ *
+ *   flags   0, EQUARX_AG_UNQUANTIZED, EQUARX_SEMI_LOOP, or both.  The other two
+ *           flags are rejected (EQUARX_BAD_SHAPE): without a quantized
+ *           reduce-scatter there is no wire to write, and a per-shard order is
+ *           built only as a single launch.
+ *           full loop: Q_B(x_0), hops 1 .. P-2, and a last launch that performs
+ *           hop P-1 and either the all-gather's quantize/dequantize pair or
+ *           (EQUARX_AG_UNQUANTIZED) the narrowing to bf16: P launches.
+ *           semi-loop (Sec. 3.3): the two half chains hop by hop, then one
+ *           launch in which the owner (partials[0]) adds the two received wires
+ *           to its own shard, counter-clockwise first: P launches.
+ *   workspace  equarx_variant_workspace_bytes(flags, P, n, block) bytes, 256-byte
+ *           aligned (the semi-loop keeps one chain's last wire while the other
+ *           chain runs: three wire buffers instead of two).
+ * Other arguments as for equarx_reduce_quantized (out_bf16 may be a partial).
+ */
+int equarx_reduce_variant_hops(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
+                               uint32_t flags, void *out_bf16, void *workspace, size_t workspace_bytes,
+                               void *stream);
+size_t equarx_variant_workspace_bytes(uint32_t flags, int32_t P, int64_t n, int32_t block);
+
+/*
  * Flat one-shot reduce: the reduce-scatter done as an all-to-all followed by
  * a local reduction (the decomposition Sec. 2 describes for ZeRO++; on a full
  * xGMI mesh, where a ring is bound by one link of seven, it is the natural

@@ -39,6 +39,8 @@ SIGNATURES = {
     "equarx_reduce_quantized_fused_ends": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp]),
     "equarx_reduce_fused": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp, _vp]),
     "equarx_reduce_variant": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp]),
+    "equarx_reduce_variant_hops": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp, _sz, _vp]),
+    "equarx_variant_workspace_bytes": (_sz, [ctypes.c_uint32, _i32, _i64, _i32]),
     "equarx_reduce_flat": (ctypes.c_int, [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp,
                                           _vp]),
     "equarx_quantize_strided": (ctypes.c_int, [_vp, _i64, _i32, _vp, _vp, _vp]),
@@ -246,6 +248,28 @@ def equarx_reduce_variant(partials, block: int, flags: int, out_bf16) -> None:
     _need(out_bf16, torch.bfloat16, n, "out_bf16")
     table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
     _check(load().equarx_reduce_variant(table, P, n, block, flags, _ptr(out_bf16), _stream()), "equarx_reduce_variant")
+
+
+def alloc_variant_workspace(flags: int, P: int, n: int, block: int) -> torch.Tensor:
+    nbytes = int(load().equarx_variant_workspace_bytes(flags, P, n, block))
+    return torch.empty(max(nbytes, 1), dtype=torch.uint8, device="cuda")
+
+
+def equarx_reduce_variant_hops(partials, block: int, flags: int, out_bf16, workspace) -> None:
+    """equarx_reduce_variant's full-loop / semi-loop forms hop by hop (one launch per hop, same bits)."""
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+        if p.numel() != n:
+            raise ValueError("partials differ in length")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    if workspace is not None and not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace: need a contiguous CUDA tensor")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().equarx_reduce_variant_hops(table, P, n, block, flags, _ptr(out_bf16), _ptr(workspace), ws_bytes,
+                                             _stream()), "equarx_reduce_variant_hops")
 
 
 def equarx_reduce_flat(local_bf16, codes_list, scales_list, block: int, out_bf16=None, codes_out=None,

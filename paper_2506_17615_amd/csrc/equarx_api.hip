@@ -133,9 +133,14 @@ void launch_head(const uint16_t *x0, const uint16_t *x1, int64_t n, int8_t *cout
 }
 
 template <int B>
-void launch_tail(const int8_t *cin, const float *sin, const uint16_t *x, int64_t n, uint16_t *out, hipStream_t s)
+void launch_tail(const int8_t *cin, const float *sin, const uint16_t *x, int64_t n, uint16_t *out, hipStream_t s,
+                 bool ag = true)
 {
-    launch(tail_kernel<B, kTilesTail>, grid_for(n, kTilesTail), s, cin, sin, x, n, out, blocks_of(n, B));
+    if (ag) {
+        launch(tail_kernel<B, kTilesTail, true>, grid_for(n, kTilesTail), s, cin, sin, x, n, out, blocks_of(n, B));
+    } else {
+        launch(tail_kernel<B, kTilesTail, false>, grid_for(n, kTilesTail), s, cin, sin, x, n, out, blocks_of(n, B));
+    }
 }
 
 // P >= 3: [Q_B(x_0) + hop 1], hops 2 .. P-2, [hop P-1 + quantize/dequantize pair]; c_i lives in wire buffer i & 1.
@@ -257,11 +262,13 @@ constexpr int kTilesFlat = EQUARX_TILES_FLAT;
 
 template <int B>
 void launch_flat(const uint16_t *local, const WireTable &tab, int R, int64_t n, uint16_t *out, int8_t *codes_out,
-                 float *scales_out, hipStream_t s)
+                 float *scales_out, hipStream_t s, bool ag = true)
 {
     const unsigned grid = grid_for(n, kTilesFlat);
     const int64_t nb = blocks_of(n, B);
-    if (out && codes_out) {
+    if (!ag) {      // bf16 output of the unquantized sum; callers pass out and no wire
+        launch(flat_kernel<B, kTilesFlat, true, false, false>, grid, s, local, tab, R, n, out, codes_out, scales_out, nb);
+    } else if (out && codes_out) {
         launch(flat_kernel<B, kTilesFlat, true, true>, grid, s, local, tab, R, n, out, codes_out, scales_out, nb);
     } else if (out) {
         launch(flat_kernel<B, kTilesFlat, true, false>, grid, s, local, tab, R, n, out, codes_out, scales_out, nb);
@@ -637,6 +644,91 @@ int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n
         EQUARX_DISPATCH_BLOCK(block, CALL)
 #undef CALL
     }
+    return launch_status();
+}
+
+size_t equarx_variant_workspace_bytes(uint32_t flags, int32_t P, int64_t n, int32_t block)
+{
+    const size_t two = equarx_workspace_bytes(P, n, block);
+    return (flags & EQUARX_SEMI_LOOP) ? two / 2 * 3 : two;      // the semi-loop keeps one chain's wire while the other runs
+}
+
+int equarx_reduce_variant_hops(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block, uint32_t flags,
+                               void *out_bf16, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int st = check_shape(n, block)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_AG_UNQUANTIZED)) return EQUARX_BAD_SHAPE;
+    const bool semi = flags & EQUARX_SEMI_LOOP, ag = !(flags & EQUARX_AG_UNQUANTIZED);
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16 || !workspace) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign) || misaligned(workspace, kWorkspaceAlign)) return EQUARX_MISALIGNED;
+    if (workspace_bytes < equarx_variant_workspace_bytes(flags, P, n, block)) return EQUARX_WORKSPACE_TOO_SMALL;
+    PartialTable tab;
+    if (int st = fill_table(partials_bf16, P, n, out_bf16, tab)) return st;
+
+    const int64_t nb = blocks_of(n, block);
+    const size_t codes = round_up((size_t)n, kWorkspaceAlign);
+    const size_t scales = round_up((size_t)nb * sizeof(float), kWorkspaceAlign);
+    char *w = static_cast<char *>(workspace);
+    int8_t *c[3];
+    float *s[3];
+    for (int i = 0; i < 3; ++i) {       // the third pair exists only in the semi-loop's larger workspace
+        c[i] = reinterpret_cast<int8_t *>(w + (size_t)i * (codes + scales));
+        s[i] = reinterpret_cast<float *>(w + (size_t)i * (codes + scales) + codes);
+    }
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    uint16_t *out = static_cast<uint16_t *>(out_bf16);
+
+    if (!semi) {
+        if (P == 1) {       // no hop: one launch quantizes/dequantizes (or copies) partial 0
+#define CALL(BB) launch_chain<BB>(tab, P, n, true, ag, false, out, nullptr, nullptr, 0, 0, hs)
+            EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+            return launch_status();
+        }
+        // Q_B(x_0), hops 1 .. P-2, then the last hop with or without the all-gather's quantize/dequantize pair
+        do_quantize(tab.x[0], n, block, c[0], s[0], hs);
+        for (int32_t i = 1; i + 1 < P; ++i) do_hop(c[(i - 1) & 1], s[(i - 1) & 1], tab.x[i], n, block, c[i & 1], s[i & 1], hs);
+#define CALL(BB) launch_tail<BB>(c[(P - 2) & 1], s[(P - 2) & 1], tab.x[P - 1], n, out, hs, ag)
+        EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+        return launch_status();
+    }
+
+    // Semi-loop (Sec. 3.3): partial 0 owns the result; the counter-clockwise chain h+1, ..., P-1 and the clockwise
+    // chain h, h-1, ..., 1 each run hop by hop and end in a wire the owner receives; the owner adds them to its
+    // own shard, counter-clockwise first.
+    const int32_t h = P / 2, na = P - 1 - h, nbk = h;
+    WireTable wires;
+    for (int32_t r = 0; r < kMaxPartials; ++r) {
+        wires.codes[r] = nullptr;
+        wires.scales[r] = nullptr;
+    }
+    int32_t received = 0;
+    int last_a = -1;
+    if (na > 0) {
+        do_quantize(tab.x[h + 1], n, block, c[0], s[0], hs);
+        for (int32_t k = 1; k < na; ++k) do_hop(c[(k - 1) & 1], s[(k - 1) & 1], tab.x[h + 1 + k], n, block, c[k & 1], s[k & 1], hs);
+        last_a = (na - 1) & 1;
+        wires.codes[received] = c[last_a];
+        wires.scales[received] = s[last_a];
+        ++received;
+    }
+    if (nbk > 0) {
+        const int u[2] = {last_a == 0 ? 1 : 0, 2};      // two buffers that do not hold the first chain's wire
+        do_quantize(tab.x[h], n, block, c[u[0]], s[u[0]], hs);
+        for (int32_t k = 1; k < nbk; ++k) {
+            do_hop(c[u[(k - 1) & 1]], s[u[(k - 1) & 1]], tab.x[h - k], n, block, c[u[k & 1]], s[u[k & 1]], hs);
+        }
+        wires.codes[received] = c[u[(nbk - 1) & 1]];
+        wires.scales[received] = s[u[(nbk - 1) & 1]];
+        ++received;
+    }
+#define CALL(BB) launch_flat<BB>(tab.x[0], wires, received, n, out, nullptr, nullptr, hs, ag)
+    EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
     return launch_status();
 }
 

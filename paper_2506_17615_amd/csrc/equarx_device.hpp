@@ -636,8 +636,9 @@ __global__ __launch_bounds__(kThreads) void head_kernel(const uint16_t *__restri
     }
 }
 
-// out = bf16( DQ( Q_B( fma(codes_in, s_in, x) ) ) ): the last hop and the quantized all-gather's pair (Sec. 3.4).
-template <int B, int K, bool kFull>
+// out = bf16( DQ( Q_B( fma(codes_in, s_in, x) ) ) ): the last hop and the quantized all-gather's pair (Sec. 3.4);
+// kAG = false: out = bf16( fma(codes_in, s_in, x) ), the all-gather left unquantized.
+template <int B, int K, bool kAG, bool kFull>
 __device__ __forceinline__ void tail_body(const int8_t *__restrict__ cin, const float *__restrict__ sin,
                                           const uint16_t *x, int64_t n, uint16_t *out,
                                           int64_t nb, int64_t wg_at)
@@ -662,20 +663,20 @@ __device__ __forceinline__ void tail_body(const int8_t *__restrict__ cin, const 
         widen_i8x8(cv[k], qf);
 #pragma unroll
         for (int j = 0; j < 8; ++j) t[j] = __builtin_fmaf(qf[j], sv[k], xf[j]);
-        finish_tile<B, true, false, kFull>(t, out, nullptr, nullptr, 0, 0, 0, wg_at + k * kTileElems + lane_at, n);
+        finish_tile<B, kAG, false, kFull>(t, out, nullptr, nullptr, 0, 0, 0, wg_at + k * kTileElems + lane_at, n);
     }
 }
 
-template <int B, int K>
+template <int B, int K, bool kAG>
 __global__ __launch_bounds__(kThreads) void tail_kernel(const int8_t *__restrict__ cin, const float *__restrict__ sin,
                                                         const uint16_t *x, int64_t n,      // out may be x (in place)
                                                         uint16_t *out, int64_t nb)
 {
     const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
     if (wg_at + kTileElems * K <= n) {
-        tail_body<B, K, true>(cin, sin, x, n, out, nb, wg_at);
+        tail_body<B, K, kAG, true>(cin, sin, x, n, out, nb, wg_at);
     } else {
-        tail_body<B, K, false>(cin, sin, x, n, out, nb, wg_at);
+        tail_body<B, K, kAG, false>(cin, sin, x, n, out, nb, wg_at);
     }
 }
 
@@ -1052,9 +1053,9 @@ struct WireTable {
     const float *scales[kMaxPartials];
 };
 
-template <int B, int K, bool kOutBf16, bool kOutWire, bool kFull>
-__device__ __forceinline__ void flat_body(const uint16_t *__restrict__ local, const WireTable &tab, int R, int64_t n,
-                                          uint16_t *__restrict__ out, int8_t *__restrict__ codes_out,
+template <int B, int K, bool kOutBf16, bool kOutWire, bool kAG, bool kFull>
+__device__ __forceinline__ void flat_body(const uint16_t *local, const WireTable &tab, int R, int64_t n,
+                                          uint16_t *out, int8_t *__restrict__ codes_out,
                                           float *__restrict__ scales_out, int64_t nb, int64_t wg_at)
 {
     constexpr int G = B / kLaneElems;
@@ -1089,6 +1090,10 @@ __device__ __forceinline__ void flat_body(const uint16_t *__restrict__ local, co
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int64_t at = wg_at + k * kTileElems + lane_at;
+        if (!kAG) {                 // all-gather left unquantized (the semi-loop's owner, Sec. 3.3/3.4): no wire out
+            store_narrowed_tile<kFull>(out, at, n, acc[k]);
+            continue;
+        }
         float q[8], s;
         quantize_lane_f<G, true>(acc[k], q, s);
         if (kOutWire) {
@@ -1104,17 +1109,17 @@ __device__ __forceinline__ void flat_body(const uint16_t *__restrict__ local, co
     }
 }
 
-template <int B, int K, bool kOutBf16, bool kOutWire>
-__global__ __launch_bounds__(kThreads) void flat_kernel(const uint16_t *__restrict__ local, const WireTable tab, int R,
-                                                        int64_t n, uint16_t *__restrict__ out,
+template <int B, int K, bool kOutBf16, bool kOutWire, bool kAG = true>
+__global__ __launch_bounds__(kThreads) void flat_kernel(const uint16_t *local, const WireTable tab, int R,
+                                                        int64_t n, uint16_t *out,
                                                         int8_t *__restrict__ codes_out, float *__restrict__ scales_out,
                                                         int64_t nb)
 {
     const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
     if (wg_at + kTileElems * K <= n) {
-        flat_body<B, K, kOutBf16, kOutWire, true>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
+        flat_body<B, K, kOutBf16, kOutWire, kAG, true>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
     } else {
-        flat_body<B, K, kOutBf16, kOutWire, false>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
+        flat_body<B, K, kOutBf16, kOutWire, kAG, false>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
     }
 }
 

@@ -53,6 +53,7 @@ def main() -> int:
     base = ref.float().to(torch.bfloat16).double()          # what an unquantized bf16 AllReduce returns
     out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
     work = eq.alloc_workspace(P, n, B)
+    work3 = eq.alloc_variant_workspace(eq.SEMI_LOOP, P, n, B)
     nb = eq.num_blocks(n, B)
     qc = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(P - 1)]
     qs = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(P - 1)]
@@ -73,6 +74,12 @@ def main() -> int:
          lambda ps: eq.equarx_reduce_fused(ps, B, out, wire_c, wire_s)),
         ("full-loop RS only", lambda ps: eq.equarx_reduce_variant(ps, B, eq.AG_UNQUANTIZED, out)),
         ("full-loop AG only", lambda ps: eq.equarx_reduce_variant(ps, B, eq.RS_UNQUANTIZED, out)),
+        ("full-loop RS only, hop by hop (P launches)",
+         lambda ps: eq.equarx_reduce_variant_hops(ps, B, eq.AG_UNQUANTIZED, out, work3)),
+        ("semi-loop RS+AG, hop by hop (P launches)",
+         lambda ps: eq.equarx_reduce_variant_hops(ps, B, eq.SEMI_LOOP, out, work3)),
+        ("semi-loop RS only, hop by hop (P launches)",
+         lambda ps: eq.equarx_reduce_variant_hops(ps, B, eq.SEMI_LOOP | eq.AG_UNQUANTIZED, out, work3)),
         ("semi-loop RS+AG", lambda ps: eq.equarx_reduce_variant(ps, B, eq.SEMI_LOOP, out)),
         ("semi-loop RS only", lambda ps: eq.equarx_reduce_variant(ps, B, eq.SEMI_LOOP | eq.AG_UNQUANTIZED, out)),
         ("full-loop RS+AG, ring order per shard", lambda ps: eq.equarx_reduce_variant(ps, B, eq.RING_ORDER, out)),

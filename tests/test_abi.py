@@ -147,6 +147,19 @@ def test_validation_rejects_before_launch(lib):
     assert rs_(ok4, 0, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(table(A, OUT + 16, A, A), 4, ns, 64, OUT, WS, 1 << 30, None) == B.STATUS_BAD_SHAPE
     assert rs_(ok4, 4, ns, 64, OUT, WS + 8, 1 << 30, None) == B.STATUS_MISALIGNED
+    vh, vw = lib.equarx_reduce_variant_hops, lib.equarx_variant_workspace_bytes
+    assert vw(0, 4, n, blk) == need and vw(B.SEMI_LOOP, 4, n, blk) == need // 2 * 3 and vw(0, 4, n, 100) == 0
+    need3 = vw(B.SEMI_LOOP, 4, n, blk)
+    for bad_flags in (B.RS_UNQUANTIZED, B.RING_ORDER, 16, B.SEMI_LOOP | B.RING_ORDER):
+        assert vh(ok4, 4, n, blk, bad_flags, OUT, WS, need3, None) == B.STATUS_BAD_SHAPE
+    assert vh(ok4, 0, n, blk, 0, OUT, WS, need3, None) == B.STATUS_BAD_SHAPE
+    assert vh(None, 4, n, blk, 0, OUT, WS, need3, None) == B.STATUS_NULL_POINTER
+    assert vh(ok4, 4, n, blk, 0, OUT, None, need3, None) == B.STATUS_NULL_POINTER
+    assert vh(ok4, 4, n, blk, 0, OUT, WS + 16, need3, None) == B.STATUS_MISALIGNED
+    assert vh(ok4, 4, n, blk, 0, OUT, WS, need - 1, None) == B.STATUS_WORKSPACE_TOO_SMALL
+    assert vh(ok4, 4, n, blk, B.SEMI_LOOP, OUT, WS, need, None) == B.STATUS_WORKSPACE_TOO_SMALL      # needs three buffers
+    assert vh(table(A, OUT + 16, A, A), 4, n, blk, B.SEMI_LOOP, OUT, WS, need3, None) == B.STATUS_BAD_SHAPE
+    assert vh(ok4, 4, n, 100, 0, OUT, WS, need3, None) == B.STATUS_BAD_BLOCK and vh(ok4, 4, 0, blk, 0, None, None, 0, None) == B.STATUS_OK
     sr = lib.equarx_selftest_rounding
     assert sr(0, 16, None, None) == B.STATUS_NULL_POINTER and sr(0, 16, A + 4, None) == B.STATUS_MISALIGNED
     assert sr(0x42FFFFFF, 2, A, None) == B.STATUS_BAD_SHAPE and sr(0, 0, None, None) == B.STATUS_OK

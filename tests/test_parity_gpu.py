@@ -560,6 +560,39 @@ def test_variant_workloads(gpu, oracle):
             assert (gpu.gpu_variant(parts, w.block, flags) == _oracle_variant(oracle, parts, w.block, flags)).all(), (case, name)
 
 
+@pytest.mark.parametrize("name", ("full", "rs_only", "semi", "semi_rs_only"))
+@pytest.mark.parametrize("P", (1, 2, 3, 4, 5, 8, 9))
+def test_variant_hop_by_hop_parity(gpu, oracle, name, P):
+    """The variants in the ring-imposed schedule (one launch per hop, wires in memory): the oracle's bits, which are
+    also the single-launch form's; output in place for odd P."""
+    flags = VARIANT_FLAGS[name]
+    n, B = 2048 * 7 + 5 * 64 + 24, 64
+    parts = [gpu.bf16_of(_values("lognormal", n, 9300 + p)) for p in range(P)]
+    want = _oracle_variant(oracle, parts, B, flags)
+    dev = [gpu.dev_bf16(p) for p in parts]
+    out = dev[P // 2] if P % 2 else torch.full((n,), 5.0, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_variant_hops(dev, B, flags, out, eq.alloc_variant_workspace(flags, P, n, B))
+    torch.cuda.synchronize()
+    assert (gpu.host_u16(out) == want).all()
+    assert (gpu.gpu_variant(parts, B, flags) == want).all()
+
+
+def test_variant_hop_by_hop_workload_shape(gpu, oracle):
+    w = wl.WORKLOADS["c3_gemma3_27b"].with_rows(40)
+    parts = [wl.as_u16(p) for p in wl.make_partials(w)]
+    oracle.set_threads(8)
+    try:
+        for name in ("rs_only", "semi", "semi_rs_only"):
+            flags = VARIANT_FLAGS[name]
+            dev = [gpu.dev_bf16(p) for p in parts]
+            out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+            eq.equarx_reduce_variant_hops(dev, w.block, flags, out, eq.alloc_variant_workspace(flags, w.P, w.n, w.block))
+            torch.cuda.synchronize()
+            assert (gpu.host_u16(out) == _oracle_variant(oracle, parts, w.block, flags)).all(), name
+    finally:
+        oracle.set_threads(1)
+
+
 def test_variant_bad_flags(gpu):
     x = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
     out = torch.empty_like(x)
