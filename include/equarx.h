@@ -205,13 +205,17 @@ int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n
  * forms above keep it in registers).  Same bits as equarx_reduce_variant with
  * the same flags.
  *
- *   flags   0, EQUARX_AG_UNQUANTIZED, EQUARX_SEMI_LOOP, or both.  The other two
- *           flags are rejected (EQUARX_BAD_SHAPE): without a quantized
- *           reduce-scatter there is no wire to write, and a per-shard order is
- *           built only as a single launch.
+ *   flags   any of EQUARX_AG_UNQUANTIZED, EQUARX_SEMI_LOOP, EQUARX_RING_ORDER,
+ *           except the last two together.  EQUARX_RS_UNQUANTIZED is rejected
+ *           (EQUARX_BAD_SHAPE): without a quantized reduce-scatter there is
+ *           no wire to write; so is the per-shard semi-loop, built only as a
+ *           single launch.
  *           full loop: Q_B(x_0), hops 1 .. P-2, and a last launch that performs
  *           hop P-1 and either the all-gather's quantize/dequantize pair or
  *           (EQUARX_AG_UNQUANTIZED) the narrowing to bf16: P launches.
+ *           full loop with EQUARX_RING_ORDER: the same P launches, each of them
+ *           one step of the ring on all P shards at once -- in step i, shard k
+ *           takes the partial of device (k + 1 + i) mod P.
  *           semi-loop (Sec. 3.3): the two half chains hop by hop, then one
  *           launch in which the owner (partials[0]) adds the two received wires
  *           to its own shard, counter-clockwise first: P launches.

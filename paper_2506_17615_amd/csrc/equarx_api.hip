@@ -153,6 +153,28 @@ void launch_fused_ends(const PartialTable &tab, int P, int64_t n, int8_t *const 
     launch_tail<B>(c[(P - 2) & 1], s[(P - 2) & 1], tab.x[P - 1], n, out, hs);
 }
 
+// Full loop in ring order, hop by hop: P launches, each over all P shards (one grid row per shard).
+template <int B>
+void launch_ring_hops(const PartialTable &tab, int P, int64_t n, bool ag, int8_t *const (&c)[3], float *const (&s)[3],
+                      uint16_t *out, hipStream_t hs)
+{
+    const int64_t nb = blocks_of(n, B);
+    const int64_t shard_elems = (nb + P - 1) / P * B;       // ceil(nb / P) blocks per shard, as the single launch
+    const unsigned gx = grid_for(shard_elems, kTilesHop), gy = (unsigned)P;
+    launch2d(quantize_ring_kernel<B, kTilesHop>, gx, gy, hs, tab, P, n, shard_elems, c[0], s[0]);
+    for (int i = 1; i + 1 < P; ++i) {
+        launch2d(hop_ring_kernel<B, kTilesHop>, gx, gy, hs, c[(i - 1) & 1], s[(i - 1) & 1], tab, P, i, n, shard_elems,
+                 c[i & 1], s[i & 1]);
+    }
+    if (ag) {
+        launch2d(tail_ring_kernel<B, kTilesHop, true>, gx, gy, hs, c[(P - 2) & 1], s[(P - 2) & 1], tab, P, P - 1, n,
+                 shard_elems, out);
+    } else {
+        launch2d(tail_ring_kernel<B, kTilesHop, false>, gx, gy, hs, c[(P - 2) & 1], s[(P - 2) & 1], tab, P, P - 1, n,
+                 shard_elems, out);
+    }
+}
+
 // Single-launch chain, measured on MI355X (27B-shaped size): 4 tiles per thread is fastest (63 us; 1, 2, 6, 8
 // tiles and 512- or 1024-thread groups are 1-8 % slower).
 #ifndef EQUARX_TILES_CHAIN
@@ -658,8 +680,10 @@ int equarx_reduce_variant_hops(const void *const *partials_bf16, int32_t P, int6
 {
     if (int st = check_shape(n, block)) return st;
     if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
-    if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_AG_UNQUANTIZED)) return EQUARX_BAD_SHAPE;
+    if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_AG_UNQUANTIZED | EQUARX_RING_ORDER)) return EQUARX_BAD_SHAPE;
     const bool semi = flags & EQUARX_SEMI_LOOP, ag = !(flags & EQUARX_AG_UNQUANTIZED);
+    const bool ring = flags & EQUARX_RING_ORDER;
+    if (semi && ring) return EQUARX_BAD_SHAPE;      // the per-shard semi-loop exists as a single launch only
     if (!partials_bf16) return EQUARX_NULL_POINTER;
     if (n == 0) return EQUARX_OK;
     if (!out_bf16 || !workspace) return EQUARX_NULL_POINTER;
@@ -683,7 +707,13 @@ int equarx_reduce_variant_hops(const void *const *partials_bf16, int32_t P, int6
 
     if (!semi) {
         if (P == 1) {       // no hop: one launch quantizes/dequantizes (or copies) partial 0
-#define CALL(BB) launch_chain<BB>(tab, P, n, true, ag, false, out, nullptr, nullptr, 0, 0, hs)
+#define CALL(BB) launch_chain<BB>(tab, P, n, true, ag, ring, out, nullptr, nullptr, 0, 0, hs)
+            EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+            return launch_status();
+        }
+        if (ring) {         // every launch is one ring step on all P shards: grid row k takes device k+1+step's partial
+#define CALL(BB) launch_ring_hops<BB>(tab, P, n, ag, c, s, out, hs)
             EQUARX_DISPATCH_BLOCK(block, CALL)
 #undef CALL
             return launch_status();

@@ -904,6 +904,62 @@ __global__ __launch_bounds__(kThreads) void chain_kernel(const PartialTable tab,
     }
 }
 
+// ---------------------------------------------------------------- ring order, hop by hop
+//
+// What all devices of a ring do in one step, as one launch: grid row k works on
+// shard k, whose chain visits devices k+1, k+2, ..., k (mod P), so in step i it
+// adds device (k + 1 + i)'s partial.  Same bodies as the plain per-pass
+// kernels; only the partial, and the end of the range, depend on the grid row.
+
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void quantize_ring_kernel(const PartialTable tab, int P, int64_t n,
+                                                                 int64_t shard_elems, int8_t *__restrict__ codes,
+                                                                 float *__restrict__ scales)
+{
+    const Span sp = workgroup_span<K>(n, shard_elems, 1);
+    if (!sp.any) return;
+    const uint16_t *x = tab.x[sp.rot >= P ? sp.rot - P : sp.rot];
+    const int64_t nb = (sp.hi + B - 1) / B;
+    if (sp.wg_at + kTileElems * K <= sp.hi) {
+        quantize_body<B, K, true>(x, sp.hi, codes, scales, nb, sp.wg_at);
+    } else {
+        quantize_body<B, K, false>(x, sp.hi, codes, scales, nb, sp.wg_at);
+    }
+}
+
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void hop_ring_kernel(const int8_t *cin, const float *sin, const PartialTable tab,
+                                                            int P, int step, int64_t n, int64_t shard_elems,
+                                                            int8_t *cout, float *sout)
+{
+    const Span sp = workgroup_span<K>(n, shard_elems, 1 + step);    // row + 1 + step < 2P
+    if (!sp.any) return;
+    const uint16_t *x = tab.x[sp.rot >= P ? sp.rot - P : sp.rot];
+    const int64_t nb = (sp.hi + B - 1) / B;
+    if (sp.wg_at + kTileElems * K <= sp.hi) {
+        hop_body<B, K, true>(cin, sin, x, sp.hi, cout, sout, nb, sp.wg_at);
+    } else {
+        hop_body<B, K, false>(cin, sin, x, sp.hi, cout, sout, nb, sp.wg_at);
+    }
+}
+
+template <int B, int K, bool kAG>
+__global__ __launch_bounds__(kThreads) void tail_ring_kernel(const int8_t *__restrict__ cin,
+                                                             const float *__restrict__ sin, const PartialTable tab,
+                                                             int P, int step, int64_t n, int64_t shard_elems,
+                                                             uint16_t *out)
+{
+    const Span sp = workgroup_span<K>(n, shard_elems, 1 + step);
+    if (!sp.any) return;
+    const uint16_t *x = tab.x[sp.rot >= P ? sp.rot - P : sp.rot];
+    const int64_t nb = (sp.hi + B - 1) / B;
+    if (sp.wg_at + kTileElems * K <= sp.hi) {
+        tail_body<B, K, kAG, true>(cin, sin, x, sp.hi, out, nb, sp.wg_at);
+    } else {
+        tail_body<B, K, kAG, false>(cin, sin, x, sp.hi, out, nb, sp.wg_at);
+    }
+}
+
 // Small messages: the same chain, organised for latency instead of bandwidth.
 // With few tiles the bandwidth-shaped kernel leaves most compute units idle
 // and pays one memory round trip per hop.  Here a workgroup takes ONE tile and

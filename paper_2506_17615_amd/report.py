@@ -83,6 +83,8 @@ def main() -> int:
         ("semi-loop RS+AG", lambda ps: eq.equarx_reduce_variant(ps, B, eq.SEMI_LOOP, out)),
         ("semi-loop RS only", lambda ps: eq.equarx_reduce_variant(ps, B, eq.SEMI_LOOP | eq.AG_UNQUANTIZED, out)),
         ("full-loop RS+AG, ring order per shard", lambda ps: eq.equarx_reduce_variant(ps, B, eq.RING_ORDER, out)),
+        ("full-loop RS+AG, ring order, hop by hop (P launches)",
+         lambda ps: eq.equarx_reduce_variant_hops(ps, B, eq.RING_ORDER, out, work3)),
         ("all-to-all: batched quantize + flat reduce", flat),
     ]
     if B in eq.STRIDED_CHUNKS and n % (1024 * B) == 0:

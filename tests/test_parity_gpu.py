@@ -560,7 +560,7 @@ def test_variant_workloads(gpu, oracle):
             assert (gpu.gpu_variant(parts, w.block, flags) == _oracle_variant(oracle, parts, w.block, flags)).all(), (case, name)
 
 
-@pytest.mark.parametrize("name", ("full", "rs_only", "semi", "semi_rs_only"))
+@pytest.mark.parametrize("name", ("full", "rs_only", "semi", "semi_rs_only", "ring", "ring_rs_only"))
 @pytest.mark.parametrize("P", (1, 2, 3, 4, 5, 8, 9))
 def test_variant_hop_by_hop_parity(gpu, oracle, name, P):
     """The variants in the ring-imposed schedule (one launch per hop, wires in memory): the oracle's bits, which are
@@ -582,7 +582,7 @@ def test_variant_hop_by_hop_workload_shape(gpu, oracle):
     parts = [wl.as_u16(p) for p in wl.make_partials(w)]
     oracle.set_threads(8)
     try:
-        for name in ("rs_only", "semi", "semi_rs_only"):
+        for name in ("rs_only", "semi", "semi_rs_only", "ring", "ring_rs_only"):
             flags = VARIANT_FLAGS[name]
             dev = [gpu.dev_bf16(p) for p in parts]
             out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
