@@ -993,3 +993,31 @@ def test_length_beyond_two_to_the_31(gpu, oracle):
         oc2, os2 = oracle.hop(oc, os_, ys, B)
         assert (c2[lo:hi].cpu().numpy() == oc2).all() and s2[b].item() == os2[0], b
         assert (out[lo:hi].view(torch.int16).cpu().numpy().view(np.uint16) == oracle.dequantize_bf16(oc2, os2, B)).all(), b
+
+
+# ----------------------------------------------------------------------------- the benchmark's output line
+
+def test_bench_prints_one_json_line_with_the_contract_keys(gpu):
+    """bench.py on the small config: exactly one line on stdout, JSON, with the keys the driver and the judge read."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    run = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "c2_gemma3_12b", "--rows", "64",
+                          "--steps", "6", "--warmup", "2", "--cpu-seconds", "1"],
+                         capture_output=True, text=True, timeout=170)
+    assert run.returncode == 0, run.stderr[-2000:]
+    lines = [l for l in run.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1, lines
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 6 and d["warmup"] == 2 and d["unit"] == "GB/s" and d["value"] > 0
+    assert d["vs_baseline"] is None and d["data"] == "synthetic" and "workload" in d["config"]
+    r = d["roofline"]
+    assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s"
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-3 and "traffic" in r
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
