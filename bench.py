@@ -144,6 +144,18 @@ def main() -> int:
         t1 = time.perf_counter()
         hop_ms_per_step = (t1 - t0) * 1e3 / K
 
+        # spread of single steps: the same K steps once more, each between two events on the stream (the records
+        # themselves cost a microsecond or two per step, so the median sits slightly above ms_per_step)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+        marks[0].record(stream)
+        for k in range(K):
+            eq.equarx_reduce_quantized(sets[k % 2], B, out, work)
+            marks[k + 1].record(stream)
+        torch.cuda.synchronize()
+        step_us = sorted(marks[k].elapsed_time(marks[k + 1]) * 1e3 for k in range(K))
+        spread = {"p10": round(step_us[int(0.1 * (K - 1))], 2), "median": round(step_us[(K - 1) // 2], 2),
+                  "p90": round(step_us[int(0.9 * (K - 1))], 2)}
+
         # hop by hop with the first two and the last two passes sharing a launch: same bits, P-1 launches
         for k in range(W):
             eq.equarx_reduce_quantized_fused_ends(sets[k % 2], B, out, work)
@@ -310,6 +322,7 @@ def main() -> int:
         "effective_input_GBps": round(gbps(2.0 * P * n, hop_ms_per_step), 1),
         "algorithmic_bytes": chain_bytes(P, n, B),
         "frac_of_hbm_peak": round(gbps(chain_bytes(P, n, B), hop_ms_per_step) / HBM_PEAK_GBPS, 4),
+        "single_step_us": spread,
     }
     fused_info = {
         "schedule": "single launch, chain in registers, no wire traffic",
