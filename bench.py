@@ -4,7 +4,8 @@
 A step is one pass of the whole hot path -- quantize, P-1 fused dequantize-add-requantize hops, final
 dequantize (equarx_reduce_quantized) -- over one batch of synthetic partial sums already resident in HBM.
 Prints ONE JSON line: effective input GB/s (bf16 bytes reduced per second), the roofline of the dominant
-kernel (the hop) from per-launch HIP event timings, and the CPU oracle timed on the host as a reported baseline.
+kernel (the hop) from HIP events recorded around runs of hops inside the real call, the other schedules with
+their own byte counts, and the CPU oracle timed on the host as a reported baseline.
 """
 from __future__ import annotations
 
