@@ -633,3 +633,57 @@ def pin_strided_geometry(lib=None):
 
 
 ALL_PINS += [pin_stage_knobs, pin_semi_loop, pin_fig7_semi_loop, pin_flat, pin_ring_order, pin_strided_geometry]
+
+
+def pin_ring_variants(lib=None):
+    """Ring layout combined with the semi-loop and with the stage knobs (Sec. 3, 3.3, 3.4).  Shard k ends on
+    device k.  Semi-loop: device k owns shard k and the devices k+1, k+2, k+3 sit around it, so the paper's
+    4-device example (device 3 sends to the owner; device 2 sends to device 1, which sends to the owner) is
+    written out once per shard with the device numbers rotated by hand.  Stage knobs: every shard equals the
+    pinned full-loop flavour run on the partials in that shard's own order, the orders spelled out."""
+    B, P = 64, 4
+    n = 64 * 7 + 20                                     # 8 blocks, 2 per shard, the last one ragged
+    parts = _chain_inputs(97, P, n)
+    x = [bf16_bits_to_f32(p) for p in parts]
+    bounds = [(0, 128), (128, 256), (256, 384), (384, n)]
+    around = {0: (1, 2, 3), 1: (2, 3, 0), 2: (3, 0, 1), 3: (0, 1, 2)}       # owner -> the devices after it on the ring
+    semi_plain = o.reduce_ring(parts, B, semi=True, quantize_ag=False, lib=lib)
+    semi_ag = o.reduce_ring(parts, B, semi=True, quantize_ag=True, lib=lib)
+    for k, (lo, hi) in enumerate(bounds):
+        d1, d2, d3 = around[k]
+        # the device before the owner sends its shard straight to it; it arrives first and is added first
+        c, s = o.quantize_bf16(parts[d3][lo:hi], B)
+        own = _fma_exact(*_dq(c, s, B), x[k][lo:hi])
+        # the device opposite the owner sends to the device after the owner, which adds its own and forwards
+        c, s = o.quantize_bf16(parts[d2][lo:hi], B)
+        t = _fma_exact(*_dq(c, s, B), x[d1][lo:hi])
+        c, s = o.quantize_f32(t, B)
+        own = _fma_exact(*_dq(c, s, B), own)
+        assert (semi_plain[lo:hi] == _bf16(own)).all(), k
+        c, s = o.quantize_f32(own, B)
+        assert (semi_ag[lo:hi] == o.dequantize_bf16(c, s, B)).all(), k
+    # the knobs reach every shard: each equals the pinned flavour on that shard's rotated inputs
+    chain_of = {0: (1, 2, 3, 0), 1: (2, 3, 0, 1), 2: (3, 0, 1, 2), 3: (0, 1, 2, 3)}     # full loop: k+1, ..., k
+    both = o.reduce_ring(parts, B, lib=lib)
+    for rs, ag in ((True, False), (False, True)):
+        got = o.reduce_ring(parts, B, quantize_rs=rs, quantize_ag=ag, lib=lib)
+        assert (got != both).any()
+        for k, (lo, hi) in enumerate(bounds):
+            want = o.reduce_stages([parts[d][lo:hi] for d in chain_of[k]], B, rs, ag)
+            assert (got[lo:hi] == want).all(), (rs, ag, k)
+    # reduce-scatter only, checked without reduce_stages on one shard: the wire that reaches device 2 is the
+    # pinned chain over devices 3, 0, 1; device 2 adds its own shard with one rounding and narrows
+    lo, hi = bounds[2]
+    _, wc, ws = o.reduce_chain([parts[d][lo:hi] for d in (3, 0, 1)], B, keep_wire=True)
+    t = _fma_exact(*_dq(wc[-1], ws[-1], B), x[2][lo:hi])
+    assert (o.reduce_ring(parts, B, quantize_ag=False, lib=lib)[lo:hi] == _bf16(t)).all()
+    # an odd ring and one that is longer than the tensor has blocks (empty shards at the end)
+    P5, n5 = 5, 32 * 3
+    parts5 = _chain_inputs(98, P5, n5)
+    got = o.reduce_ring(parts5, 32, semi=True, lib=lib)
+    for k, order in enumerate(((0, 1, 2, 3, 4), (1, 2, 3, 4, 0), (2, 3, 4, 0, 1))):
+        lo, hi = 32 * k, 32 * (k + 1)
+        assert (got[lo:hi] == o.reduce_semi_loop([parts5[d][lo:hi] for d in order], 32, True)).all(), k
+
+
+ALL_PINS += [pin_ring_variants]

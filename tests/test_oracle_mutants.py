@@ -92,3 +92,56 @@ def test_unmutated_copy_passes(oracle, tmp_path):
     src = os.path.join(os.path.dirname(o.__file__), "equarx_oracle.c")
     lib = o.load(o.build(force=True, src=src, lib=str(tmp_path / "libcopy.so")))
     assert _failing_pins(lib) == []
+
+
+# ----------------------------------------------------------------------------------------------------------
+# The ring layout (shard split, per-shard rotation, pass-through of the semi-loop flag and the stage knobs) is
+# composed in the oracle's Python front end, so its mistakes are planted there: a mutated copy of the module is
+# imported from a temporary file and its reduce_ring / ring_order / shard_bounds stand in for the real ones.
+
+PY_MUTANTS = {
+    "ring_semi_owner_is_next_device": ("order = [(k + j) % P for j in range(P)]", "order = [(k + 1 + j) % P for j in range(P)]"),
+    "ring_semi_walks_backwards": ("order = [(k + j) % P for j in range(P)]", "order = [(k - j) % P for j in range(P)]"),
+    "ring_semi_not_rotated": ("order = [(k + j) % P for j in range(P)]", "order = list(range(P))"),
+    "ring_semi_drops_ag_knob": ("reduce_semi_loop([arrs[d][lo:hi] for d in order], B, quantize_ag, lib=lib)",
+                                "reduce_semi_loop([arrs[d][lo:hi] for d in order], B, True, lib=lib)"),
+    "ring_drops_rs_knob": ("B, quantize_rs, quantize_ag, lib=lib)", "B, True, quantize_ag, lib=lib)"),
+    "ring_drops_ag_knob": ("B, quantize_rs, quantize_ag, lib=lib)", "B, quantize_rs, True, lib=lib)"),
+    "ring_swaps_knobs": ("B, quantize_rs, quantize_ag, lib=lib)", "B, quantize_ag, quantize_rs, lib=lib)"),
+    "ring_ignores_semi_flag": ("        if semi:\n            order", "        if False:\n            order"),
+    "ring_starts_at_own_device": ("return [(shard + 1 + i) % P for i in range(P)]", "return [(shard + i) % P for i in range(P)]"),
+    "ring_walks_backwards": ("return [(shard + 1 + i) % P for i in range(P)]", "return [(shard - 1 - i) % P for i in range(P)]"),
+    "shards_not_on_block_boundaries": ("per = (nb + P - 1) // P\n    return [(min(n, k * per * B), min(n, (k + 1) * per * B)) for k in range(P)]",
+                                       "per = (n + P - 1) // P\n    return [(min(n, k * per), min(n, (k + 1) * per)) for k in range(P)]"),
+}
+
+
+def _mutated_front_end(tmp_path, old, new):
+    import importlib.util
+
+    with open(o.__file__) as f:
+        src = f.read()
+    assert src.count(old) == 1, "mutation site not found exactly once"
+    path = tmp_path / "equarx_oracle_mutant.py"
+    path.write_text(src.replace(old, new))
+    spec = importlib.util.spec_from_file_location("equarx_oracle_mutant", str(path))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    mod._lib = o._L()           # the C library is the real, unmutated one
+    return mod
+
+
+@pytest.mark.parametrize("name", sorted(PY_MUTANTS))
+def test_pins_catch_front_end_mutant(oracle, tmp_path, monkeypatch, name):
+    mod = _mutated_front_end(tmp_path, *PY_MUTANTS[name])
+    for attr in ("reduce_ring", "ring_order", "shard_bounds"):
+        monkeypatch.setattr(o, attr, getattr(mod, attr))
+    failed = _failing_pins(None, first_only=True)
+    assert failed, f"no pin noticed the planted mistake {name!r}"
+
+
+def test_unmutated_front_end_copy_passes(oracle, tmp_path, monkeypatch):
+    mod = _mutated_front_end(tmp_path, "import ctypes\n", "import ctypes  \n")
+    for attr in ("reduce_ring", "ring_order", "shard_bounds"):
+        monkeypatch.setattr(o, attr, getattr(mod, attr))
+    assert [p for p in ("pin_ring_order", "pin_ring_variants") if p in _failing_pins(None)] == []
