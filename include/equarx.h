@@ -19,7 +19,17 @@
  *     Work is enqueued on it; no entry point synchronises.
  *   - Return value: an equarx_status.  A call that fails validation launches
  *     nothing and touches no memory.  n == 0 is valid and does nothing;
- *     n above 2^40 is EQUARX_BAD_SHAPE.
+ *     n above 2^40 is EQUARX_BAD_SHAPE.  EQUARX_DEVICE_ERROR reports what the
+ *     call's own kernel launches returned (a chain stops launching at the
+ *     first failure); an error some earlier HIP call left pending on the
+ *     thread is neither reported nor cleared.
+ *   - Sharing memory between the buffers of one call: a buffer the call
+ *     WRITES (an output, the workspace, a kept wire) may not overlap any other
+ *     buffer of the call, not even partly -- EQUARX_BAD_SHAPE -- except where
+ *     an entry point says that an output may BE an input; the two must then
+ *     coincide exactly.  Buffers that are only read may overlap freely.
+ *   - The library keeps no state between calls and may be called from several
+ *     threads at once (on different streams, or on one).
  *   - Pointers must be 16-byte aligned (8-byte for codes, 4 for scales is not
  *     enough: every data pointer is checked against 16).
  *   - Supported block sizes: 32, 64, 128, 256, 512.
@@ -42,7 +52,7 @@ typedef enum equarx_status {
     EQUARX_BAD_BLOCK = 3,           /* block not in {32, 64, 128, 256, 512} */
     EQUARX_MISALIGNED = 4,          /* a data pointer is not 16-byte aligned */
     EQUARX_WORKSPACE_TOO_SMALL = 5, /* workspace_bytes < equarx_workspace_bytes(...) */
-    EQUARX_DEVICE_ERROR = 6         /* the HIP runtime reported an error at launch */
+    EQUARX_DEVICE_ERROR = 6         /* a kernel launch of this call returned a HIP error */
 } equarx_status;
 
 #define EQUARX_MAX_PARTIALS 64
@@ -68,7 +78,8 @@ int equarx_quantize(const void *x_bf16, int64_t n, int32_t block,
  *
  *   x_bf16, codes, scales   HOST arrays of `count` device pointers
  *                           (0 <= count <= EQUARX_MAX_PARTIALS), read before
- *                           the call returns; no two tensors may share an output.
+ *                           the call returns; no output may overlap another
+ *                           output or any input (EQUARX_BAD_SHAPE).
  */
 int equarx_quantize_batch(const void *const *x_bf16, int8_t *const *codes, float *const *scales, int32_t count,
                           int64_t n, int32_t block, void *stream);
@@ -91,8 +102,9 @@ int equarx_dequantize(const int8_t *codes, const float *scales, int64_t n, int32
  *   t = fma(fp32(codes_in), scales_in[block], fp32(local))   (one rounding)
  *   (codes_out, scales_out) = quantize(t) as in equarx_quantize.
  *
- * codes_out may alias codes_in and scales_out may alias scales_in (each block
- * is read completely before it is written); no other aliasing is allowed.
+ * codes_out may BE codes_in and scales_out may BE scales_in (each block is read
+ * completely before it is written); any other overlap between what the call
+ * writes and its other buffers is EQUARX_BAD_SHAPE.
  */
 int equarx_reduce_stage(const int8_t *codes_in, const float *scales_in, const void *local_bf16,
                         int64_t n, int32_t block,
@@ -249,7 +261,7 @@ size_t equarx_variant_workspace_bytes(uint32_t flags, int32_t P, int64_t n, int3
  *   out_bf16 [n]       device or NULL.
  *   codes_out [n], scales_out [nb]   device or both NULL; at least one of
  *                      out_bf16 and the (codes_out, scales_out) pair must be given.
- * Outputs must not alias inputs.
+ * No output may overlap an input or another output (EQUARX_BAD_SHAPE).
  */
 int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const float *const *scales, int32_t R,
                        int64_t n, int32_t block, void *out_bf16, int8_t *codes_out, float *scales_out,
@@ -272,7 +284,7 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
  *            1024 * chunks (else EQUARX_BAD_SHAPE).  scales has n / chunks entries.
  *   equarx_reduce_quantized_strided: the hop-by-hop chain (P+1 launches);
  *            workspace of equarx_workspace_bytes(P, n, chunks) bytes, 256-byte aligned.
- *   equarx_reduce_stage_strided: codes_out / scales_out may alias the inputs.
+ *   equarx_reduce_stage_strided: codes_out / scales_out may BE codes_in / scales_in.
  *   equarx_reduce_fused_strided: the same chain in one launch (running sums in
  *            registers, no wire traffic, no workspace); same bits.
  */
@@ -301,69 +313,6 @@ int64_t equarx_wire_row_scales(int64_t n, int32_t block);
 
 /* Static, NUL-terminated description of a status code. */
 const char *equarx_status_string(int status);
-
-/* Plain 16-byte-vector device copy of `bytes` bytes (a multiple of 16, both
- * pointers 16-byte aligned): the calibration kernel the benchmark uses to
- * find the HBM bandwidth a streaming kernel can reach on this device. */
-int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
-
-/* The chain's hops as memory traffic only: P-1 launches of a kernel with
- * exactly the loads and stores of equarx_reduce_stage (same tiling, same
- * access widths, the same ping-pong between two wire buffers, partial i read by
- * launch i) whose only computation is an XOR -- the time the memory system
- * alone needs for a hop, which the benchmark sets beside the hop kernel's.
- * n must be a multiple of block.  (codes0, scales0) is the input of launch 1,
- * which writes (codes1, scales1); launch 2 reads those and writes buffer 0,
- * and so on.  Per launch and per 8 consecutive elements (the partial as four
- * little-endian 32-bit words X0..X3, the codes read as two words C0, C1):
- * codes written = (X0^X2^C0, X1^X3^C1); scales written = scales read. */
-int equarx_calib_hop_traffic(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
-                             int8_t *codes0, float *scales0, int8_t *codes1, float *scales1, void *stream);
-
-/*
- * Self-tests of the kernels' arithmetic (used by the test suite).
- *
- * The quantizer needs, per block, scale = fl32(absmax / 127) and
- * inv = fl32(127 / absmax), correctly rounded (Sec. 3.2 leaves the formula
- * open; these are the readings the library documents).  The kernels compute
- * them with short reciprocal-based sequences instead of a full IEEE division.
- *
- * equarx_selftest_quotients compares those sequences with the IEEE division on
- * the device for the `count` consecutive fp32 bit patterns starting at
- * first_bits (positive, finite: first_bits + count <= 0x7F800000) and ADDS the
- * number of differing scales to mismatches[0] and of differing reciprocals to
- * mismatches[1] (device pointer, two uint64, zeroed by the caller).
- *
- * equarx_eval_quotients evaluates them for n caller-given values (device
- * arrays absmax[n] -> scale[n], inv[n]) so that a host can compare them with
- * its own division.
- */
-int equarx_selftest_quotients(uint32_t first_bits, uint64_t count, uint64_t *mismatches, void *stream);
-
-/* The kernels take the int8 code of a scaled value p (|p| <= 127 up to
- * rounding) from the low byte of fl32(p + 1.5 * 2^23) instead of rounding,
- * converting and masking.  This compares the two, for +p and -p, over `count`
- * consecutive fp32 bit patterns of |p| from first_bits (first_bits + count <=
- * 0x43000000, i.e. |p| < 128) and adds the number of differences to
- * mismatches[0] (device pointer, one uint64, zeroed by the caller). */
-int equarx_selftest_rounding(uint32_t first_bits, uint64_t count, uint64_t *mismatches, void *stream);
-int equarx_eval_quotients(const float *absmax, int64_t n, float *scale, float *inv, void *stream);
-
-/* Profiling aid.  The next kernel the calling thread launches through this
- * library (whichever entry point launches it) carries the two hipEvent_t
- * handles, passed as void*: after the stream has been synchronised,
- * hipEventElapsedTime(start, stop) is that one kernel's execution time.
- * The setting applies to exactly one launch; either handle may be NULL. */
-void equarx_time_next_launch(void *start_event, void *stop_event);
-
-/* Profiling aid for an entry point that launches several kernels.  Counting
- * the calling thread's coming launches from 0, `start_event` is recorded on
- * the launch's stream (hipEventRecord) just before launch `first` and
- * `stop_event` just after launch `last` (last >= first >= 0): the elapsed time
- * is that of launches first..last back to back, with nothing attached to the
- * kernels themselves.  E.g. hops 1..P-1 of equarx_reduce_quantized are its
- * launches 1..P-1.  One setting is pending at a time; invalid arguments cancel it. */
-void equarx_time_launch_span(int32_t first, int32_t last, void *start_event, void *stop_event);
 
 #ifdef __cplusplus
 }

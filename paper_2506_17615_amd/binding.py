@@ -27,7 +27,7 @@ MAX_PARTIALS = 64
 BLOCK_SIZES = (32, 64, 128, 256, 512)
 SEMI_LOOP, RS_UNQUANTIZED, AG_UNQUANTIZED, RING_ORDER = 1, 2, 4, 8
 
-# name -> (restype, argtypes); mirrors include/equarx.h
+# name -> (restype, argtypes); SIGNATURES mirrors include/equarx.h, DEVTOOLS_SIGNATURES include/equarx_devtools.h
 _vp, _i64, _i32, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
 SIGNATURES = {
     "equarx_quantize": (ctypes.c_int, [_vp, _i64, _i32, _vp, _vp, _vp]),
@@ -53,13 +53,16 @@ SIGNATURES = {
     "equarx_wire_row_codes": (_i64, [_i64]),
     "equarx_wire_row_scales": (_i64, [_i64, _i32]),
     "equarx_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+}
+DEVTOOLS_SIGNATURES = {
     "equarx_calib_hop_traffic": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp]),
-    "equarx_time_launch_span": (None, [_i32, _i32, _vp, _vp]),
     "equarx_calib_copy": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
-    "equarx_time_next_launch": (None, [_vp, _vp]),
     "equarx_selftest_quotients": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint64, _vp, _vp]),
     "equarx_selftest_rounding": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint64, _vp, _vp]),
     "equarx_eval_quotients": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp]),
+    "equarx_time_launch_span": (None, [_i32, _i32, _vp, _vp]),
+    "equarx_time_next_launch": (None, [_vp, _vp]),
+    "equarx_time_cancel": (None, []),
 }
 
 
@@ -83,7 +86,7 @@ def load() -> ctypes.CDLL:
                 f"{path} is missing: build it first (python -m paper_2506_17615_amd.build); "
                 "there is no fallback path")
         lib = ctypes.CDLL(path)
-        for name, (res, args) in SIGNATURES.items():
+        for name, (res, args) in {**SIGNATURES, **DEVTOOLS_SIGNATURES}.items():
             fn = getattr(lib, name)
             fn.restype = res
             fn.argtypes = args
@@ -387,13 +390,19 @@ def equarx_calib_hop_traffic(partials, block: int, codes0, scales0, codes1, scal
 
 
 def equarx_time_launch_span(first: int, last: int, start_event, stop_event) -> None:
-    """Raw hipEvent_t handles recorded before the thread's launch `first` and after its launch `last` (from 0)."""
+    """Raw hipEvent_t handles recorded before launch `first` and after launch `last` (from 0) of this thread's
+    next call."""
     load().equarx_time_launch_span(first, last, start_event, stop_event)
 
 
 def equarx_time_next_launch(start_event, stop_event) -> None:
-    """start/stop: raw hipEvent_t handles (ints); the next launch on this thread records its begin and end there."""
+    """start/stop: raw hipEvent_t handles (ints); the first launch of this thread's next call records its begin and
+    end there."""
     load().equarx_time_next_launch(start_event, stop_event)
+
+
+def equarx_time_cancel() -> None:
+    load().equarx_time_cancel()
 
 
 def equarx_selftest_quotients(first_bits: int, count: int, mismatches: torch.Tensor) -> None:

@@ -8,7 +8,8 @@ import pytest
 
 from paper_2506_17615_amd import binding, build
 
-HEADER = os.path.join(os.path.dirname(build.INCLUDE), "include", "equarx.h")
+HEADER = os.path.join(build.INCLUDE, "equarx.h")
+DEVTOOLS_HEADER = os.path.join(build.INCLUDE, "equarx_devtools.h")
 
 
 @pytest.fixture(scope="module")
@@ -18,8 +19,8 @@ def lib():
     return binding.load()
 
 
-def declared_functions():
-    text = open(HEADER).read()
+def declared_functions(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(equarx_[a-z0-9_]+)\s*\(", text)))
 
@@ -28,8 +29,13 @@ def test_header_and_binding_agree(lib):
     names = declared_functions()
     assert "equarx_quantize" in names and "equarx_reduce_quantized" in names
     assert set(names) == set(binding.SIGNATURES), "binding.SIGNATURES must list exactly the header's functions"
-    for name in names:
-        assert hasattr(lib, name), f"{name} declared in equarx.h but not exported"
+    dev = declared_functions(DEVTOOLS_HEADER)
+    assert set(dev) == set(binding.DEVTOOLS_SIGNATURES), "binding.DEVTOOLS_SIGNATURES must list exactly equarx_devtools.h"
+    assert not set(dev) & set(names)
+    for name in names + dev:
+        assert hasattr(lib, name), f"{name} declared in a header but not exported"
+    # the product header declares the method's calls and size queries only: no calibration, self-test or timing aid
+    assert not [n for n in names if re.search(r"calib|selftest|time_|eval_", n)]
 
 
 def test_status_strings(lib):
@@ -222,6 +228,117 @@ def test_validation_rejects_before_launch(lib):
     assert cp(A, ODD, 64, None) == B.STATUS_MISALIGNED
 
 
+def test_overlapping_buffers_are_rejected_before_launch(lib):
+    """Every buffer a call writes must be disjoint from the call's other buffers unless the header says the two may
+    BE the same buffer: partial overlaps, an output inside an input, a workspace over the output -- all
+    EQUARX_BAD_SHAPE, decided on the host from the addresses (none is ever dereferenced here)."""
+    B = binding
+    BAD = B.STATUS_BAD_SHAPE
+
+    def table(*ptrs):
+        return (ctypes.c_void_p * len(ptrs))(*ptrs)
+
+    n, blk = 4096, 256                      # codes 4096 B, scales 64 B, bf16 8192 B
+    X, C, S, OUT = A, A + 0x10000, A + 0x20000, A + 0x30000
+    q, d, st = lib.equarx_quantize, lib.equarx_dequantize, lib.equarx_reduce_stage
+    assert q(X, n, blk, X, S, None) == BAD                       # codes over the input
+    assert q(X, n, blk, X + 8192 - 16, S, None) == BAD           # codes start inside the input's last 16 bytes
+    assert q(X, n, blk, C, C + 4096 - 16, None) == BAD           # scales start inside the codes
+    assert q(X, n, blk, C, X + 16, None) == BAD                  # scales inside the input
+    assert d(C, S, n, blk, C, None) == BAD                       # output over the codes
+    assert d(C, S, n, blk, S - 8192 + 16, None) == BAD           # output's tail reaches the scales
+    C2, S2, L = A + 0x40000, A + 0x50000, A + 0x60000
+    assert st(C, S, L, n, blk, C + 16, S2, None) == BAD          # wire updated "in place" but shifted
+    assert st(C, S, L, n, blk, C2, S + 16, None) == BAD
+    assert st(C, S, L, n, blk, L, S2, None) == BAD               # codes written over the local shard
+    assert st(C, S, L, n, blk, C2, L + 4096, None) == BAD        # scales written into the local shard
+    assert st(C, S, L, n, blk, S - 4096 + 16, S2, None) == BAD   # codes_out reaches into scales_in
+    assert st(C, S, L, n, blk, C2, C2 + 1024, None) == BAD       # the two outputs overlap each other
+    assert st(C, S, L, n, blk, S, C, None) == BAD                # outputs swapped onto the inputs: not the same role
+    for fn in (lib.equarx_quantize_strided,):
+        ns = 1024 * 64
+        assert fn(X, ns, 64, X + 2 * ns - 16, S + 0x100000, None) == BAD
+    ns = 1024 * 64
+    assert lib.equarx_dequantize_strided(C, C + ns + 0x1000, ns, 64, C + 16, None) == BAD
+    assert lib.equarx_reduce_stage_strided(C, A + 0x200000, A + 0x300000, ns, 64, C + 1024, A + 0x400000, None) == BAD
+
+    need = B.workspace_bytes(4, n, blk)
+    ok4 = table(A, A + 0x10000, A + 0x20000, A + 0x30000)
+    OUT, WS = A + 0x100000, A + 0x200000
+    chains = [
+        lambda parts, out, ws: lib.equarx_reduce_quantized(parts, 4, n, blk, out, ws, need, None, None, None),
+        lambda parts, out, ws: lib.equarx_reduce_quantized_fused_ends(parts, 4, n, blk, out, ws, need, None),
+        lambda parts, out, ws: lib.equarx_reduce_variant_hops(parts, 4, n, blk, 0, out, ws, need, None),
+        lambda parts, out, ws: lib.equarx_reduce_variant_hops(parts, 4, n, blk, B.AG_UNQUANTIZED, out, ws, need, None),
+    ]
+    for call in chains:
+        assert call(ok4, OUT, OUT) == BAD                        # workspace = output
+        assert call(ok4, OUT, OUT + 8192 - 256) == BAD           # workspace starts inside the output
+        assert call(ok4, WS + need - 256, WS) == BAD             # output starts inside the workspace
+        assert call(ok4, OUT, A + 0x20000) == BAD                # workspace over a partial
+        assert call(ok4, OUT, A + 0x20000 - need + 256) == BAD   # workspace's tail reaches a partial
+        assert call(table(A, A, OUT + 16, A), OUT, WS) == BAD    # output overlaps a partial without being it
+    need3 = lib.equarx_variant_workspace_bytes(B.SEMI_LOOP, 4, n, blk)
+    assert lib.equarx_reduce_variant_hops(ok4, 4, n, blk, B.SEMI_LOOP, OUT, OUT - need3 + 256, need3, None) == BAD
+    ns = 1024 * 64
+    needs = B.workspace_bytes(4, ns, 64)
+    oks = table(A, A + 0x100000, A + 0x200000, A + 0x300000)
+    assert lib.equarx_reduce_quantized_strided(oks, 4, ns, 64, A + 0x400000, A + 0x400000 + 2 * ns - 256, needs, None) == BAD
+    assert lib.equarx_reduce_quantized_strided(oks, 4, ns, 64, A + 0x400000, A + 0x200000, needs, None) == BAD
+    # kept wire: [P][row] arrays the chain writes
+    rc, rs = B.wire_row_codes(n), B.wire_row_scales(n, blk)
+    WC, WSC = A + 0x300000, A + 0x400000
+    rq, rf = lib.equarx_reduce_quantized, lib.equarx_reduce_fused
+    assert rq(ok4, 4, n, blk, OUT, None, 0, OUT, WSC, None) == BAD                       # wire codes over the output
+    assert rq(ok4, 4, n, blk, OUT, None, 0, WC, WC + 4 * rc - 16, None) == BAD           # scales start inside the codes' last row
+    assert rq(ok4, 4, n, blk, OUT, None, 0, A + 0x10000 - 4 * rc + 16, WSC, None) == BAD # wire codes reach into partial 1
+    assert rq(ok4, 4, n, blk, WSC + 16, None, 0, WC, WSC, None) == BAD                   # output inside the wire scales
+    assert rf(ok4, 4, n, blk, OUT, OUT + 4096, WSC, None) == BAD
+    assert rf(ok4, 4, n, blk, OUT, WC, A + 0x30000 + 8192 - 16, None) == BAD             # wire scales over partial 3's end
+    assert rf(ok4, 4, n, blk, OUT, WC, WC + 16, None) == BAD
+    # flat: nothing written may share memory with anything read or with another output
+    fl = lib.equarx_reduce_flat
+    LOC = A + 0x40000
+    ctab, stab = table(A, A + 0x10000), table(A + 0x20000, A + 0x30000)
+    CO, SO = A + 0x500000, A + 0x600000
+    assert fl(LOC, ctab, stab, 2, n, blk, LOC + 16, None, None, None) == BAD             # output overlaps the local shard
+    assert fl(LOC, ctab, stab, 2, n, blk, A + 0x10000 - 8192 + 16, None, None, None) == BAD    # output's tail in codes[1]
+    assert fl(LOC, ctab, stab, 2, n, blk, OUT, A, SO, None) == BAD                       # codes_out = a received shard
+    assert fl(LOC, ctab, stab, 2, n, blk, OUT, A + 2048, SO, None) == BAD                # ... or half way into it
+    assert fl(LOC, ctab, stab, 2, n, blk, OUT, CO, A + 0x30000, None) == BAD             # scales_out = received scales
+    assert fl(LOC, ctab, stab, 2, n, blk, OUT, OUT + 4096, SO, None) == BAD              # two outputs overlap
+    assert fl(LOC, ctab, stab, 2, n, blk, None, CO, CO + 4096 - 16, None) == BAD
+    assert fl(LOC, ctab, stab, 2, n, blk, OUT, LOC + 4096, SO, None) == BAD              # codes_out in the local shard
+    # batch quantize: every output against every input and every other output
+    qb = lib.equarx_quantize_batch
+    xs = table(A, A + 0x10000)
+    assert qb(xs, table(A + 0x20000, A + 0x20000 + 2048), table(A + 0x40000, A + 0x50000), 2, n, blk, None) == BAD
+    assert qb(xs, table(A + 0x20000, A + 0x30000), table(A + 0x40000, A + 0x40000 + 32), 2, n, blk, None) == BAD
+    assert qb(xs, table(A + 0x20000, A + 0x10000 + 4096), table(A + 0x40000, A + 0x50000), 2, n, blk, None) == BAD
+    assert qb(xs, table(A + 0x20000, A + 0x30000), table(A + 16, A + 0x50000), 2, n, blk, None) == BAD
+    assert qb(xs, table(A + 0x20000, A + 0x30000), table(A + 0x30000 + 4096 - 16, A + 0x50000), 2, n, blk, None) == BAD
+    # developer aids follow the same rule
+    assert lib.equarx_calib_copy(A, A + 64, 128, None) == BAD and lib.equarx_calib_copy(A, A, 128, None) == BAD
+    ht = lib.equarx_calib_hop_traffic
+    C0, C1 = A + 0x300000, A + 0x400000
+    assert ht(ok4, 4, n, blk, C0, C0 + 0x1000, C0 + 2048, C1 + 0x1000, None) == BAD
+    assert ht(ok4, 4, n, blk, C0, C0 + 0x1000, C1, C0 + 0x1000 + 16, None) == BAD
+    assert ht(ok4, 4, n, blk, A + 0x20000 + 4096, C0 + 0x1000, C1, C1 + 0x1000, None) == BAD
+
+
+def test_timing_hooks_do_not_outlive_the_next_call(lib):
+    """A span or launch hook armed before a call that fails validation is dropped by that call: nothing stays
+    pending for a later, unrelated call (checked through the library's own bookkeeping: arming, a rejected call,
+    and equarx_time_cancel all return, and a second rejected call behaves the same)."""
+    E0, E1 = A + 0x700000, A + 0x700100     # never used as events: every call below fails validation first
+    lib.equarx_time_launch_span(0, 3, E0, E1)
+    lib.equarx_time_next_launch(E0, E1)
+    assert lib.equarx_quantize(A, 4096, 100, A, A, None) == binding.STATUS_BAD_BLOCK       # consumes and drops the hooks
+    assert lib.equarx_quantize(None, 4096, 256, A, A, None) == binding.STATUS_NULL_POINTER
+    lib.equarx_time_launch_span(2, 1, E0, E1)          # invalid: cancels
+    lib.equarx_time_cancel()
+
+
 def test_missing_library_is_an_error(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(build, "LIB_PATH", str(tmp_path / "nope.so"))
@@ -233,10 +350,11 @@ def test_header_is_plain_c(tmp_path):
     """include/equarx.h is a C header: a C99 translation unit that includes it and takes the address of every
     declared function compiles with gcc (no C++, no HIP, no torch types in the signatures)."""
     import subprocess
-    names = declared_functions()
+    names = declared_functions() + declared_functions(DEVTOOLS_HEADER)
     src = tmp_path / "use_header.c"
     body = "\n".join(f"    p[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
-    src.write_text(f'#include "equarx.h"\nvoid (*p[{len(names)}])(void);\nvoid take(void) {{\n{body}\n}}\n')
+    src.write_text(f'#include "equarx.h"\n#include "equarx_devtools.h"\nvoid (*p[{len(names)}])(void);\n'
+                   f'void take(void) {{\n{body}\n}}\n')
     subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-c", str(src), "-I", os.path.dirname(HEADER),
                     "-o", str(tmp_path / "use_header.o")], check=True)
 

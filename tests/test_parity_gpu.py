@@ -342,6 +342,51 @@ def test_time_launch_span_brackets_the_hops(gpu, oracle):
     assert (gpu.host_u16(out) == want).all()
 
 
+def test_timing_hooks_die_with_a_rejected_call(gpu, oracle):
+    """Hooks armed before a call that fails validation are dropped by that call: the next, valid call neither
+    records nor attaches them (the events keep the times of their own earlier records)."""
+    w = wl.WORKLOADS["c1_small"]
+    parts = [p.reshape(-1).cuda() for p in wl.make_partials(w)]
+    out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+    work = eq.alloc_workspace(w.P, w.n, w.block)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    b.record()
+    torch.cuda.synchronize()
+    before = a.elapsed_time(b)
+    for arm in (lambda: eq.equarx_time_launch_span(0, w.P, a.cuda_event, b.cuda_event),
+                lambda: eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)):
+        arm()
+        with pytest.raises(eq.EquarxError) as err:
+            eq.equarx_reduce_quantized(parts, 48, out, work)         # unsupported block size: rejected on the host
+        assert err.value.status == eq.STATUS_BAD_BLOCK
+        eq.equarx_reduce_quantized(parts, w.block, out, work)
+        eq.equarx_reduce_fused(parts, w.block, out)
+        torch.cuda.synchronize()
+        assert a.elapsed_time(b) == before
+    assert (gpu.host_u16(out) == oracle.reduce_chain([wl.as_u16(p) for p in wl.make_partials(w)], w.block)).all()
+
+
+def test_stale_hip_error_is_not_reported_as_ours(gpu):
+    """An error an unrelated HIP call left pending on the thread does not turn a good launch into
+    EQUARX_DEVICE_ERROR: the status comes from the launch call's own return value."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipGetLastError.restype = ctypes.c_int
+    hip.hipFree.restype = ctypes.c_int
+    hip.hipFree.argtypes = [ctypes.c_void_p]
+    hip.hipGetLastError()                                   # start clean
+    x = torch.randn(4096, device="cuda").to(torch.bfloat16)
+    codes = torch.empty(4096, dtype=torch.int8, device="cuda")
+    scales = torch.empty(16, dtype=torch.float32, device="cuda")
+    assert hip.hipFree(ctypes.c_void_p(0x10)) != 0          # an invalid free: returns an error and leaves it pending
+    eq.equarx_quantize(x, 256, codes, scales)               # would raise on EQUARX_DEVICE_ERROR
+    torch.cuda.synchronize()
+    hip.hipGetLastError()                                   # leave the thread clean for the tests that follow
+    assert hip.hipGetLastError() == 0
+    assert int(codes.abs().max()) == 127
+
+
 @pytest.mark.parametrize("P,n,B", ((4, 2048 * 5 + 300, 64), (8, 24 * 5376, 256)))
 def test_plain_c_client_drives_the_path(gpu, oracle, tmp_path, P, n, B):
     """The C ABI without Python in between: a C99 program (tests/abi_client.c) allocates with the HIP runtime,
