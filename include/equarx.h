@@ -145,6 +145,31 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
                             int8_t *wire_codes, float *wire_scales, void *stream);
 
 /*
+ * equarx_reduce_quantized for callers that cannot allocate device memory and
+ * have no workspace to hand in: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same kernels, same P+1 launches,
+ * same bits; the two ping-pong wire buffers live in a static device array of
+ * EQUARX_STATIC_WORKSPACE_BYTES that each GPU the library runs on holds from
+ * the moment the library is loaded there until the process ends.  The call
+ * allocates and frees nothing, on the device or through any library.
+ *
+ *   - equarx_workspace_bytes(P, n, block) above EQUARX_STATIC_WORKSPACE_BYTES
+ *     is EQUARX_WORKSPACE_TOO_SMALL (80 MiB covers 64 Mi elements at block 32
+ *     and every configuration of the benchmark list).
+ *   - The first call on a GPU looks the array's address up
+ *     (hipGetSymbolAddress; EQUARX_DEVICE_ERROR if that fails); make it
+ *     outside a graph capture.
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels
+ *     may run at the same time (different streams, different threads) RACE
+ *     on it.  Calls on one stream, or ordered by events, are safe; nothing in
+ *     the array needs clearing between calls, whatever their sizes.
+ * Other arguments as for equarx_reduce_quantized, without the kept wire.
+ */
+#define EQUARX_STATIC_WORKSPACE_BYTES (80u << 20)
+int equarx_reduce_quantized_static(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
+                                   void *out_bf16, void *stream);
+
+/*
  * The same hop-by-hop chain with its two ends fused: the first launch
  * quantizes partial 0 in registers and performs hop 1, the last launch performs
  * hop P-1 and the quantize/dequantize pair of the quantized all-gather

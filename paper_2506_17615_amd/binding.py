@@ -36,6 +36,7 @@ SIGNATURES = {
     "equarx_dequantize": (ctypes.c_int, [_vp, _vp, _i64, _i32, _vp, _vp]),
     "equarx_reduce_stage": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "equarx_reduce_quantized": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp, _vp, _vp]),
+    "equarx_reduce_quantized_static": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp]),
     "equarx_reduce_quantized_fused_ends": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp]),
     "equarx_reduce_fused": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp, _vp]),
     "equarx_reduce_variant": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp]),
@@ -204,6 +205,23 @@ def equarx_reduce_quantized(partials, block: int, out_bf16, workspace=None, wire
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().equarx_reduce_quantized(table, P, n, block, _ptr(out_bf16), _ptr(workspace), ws_bytes,
                                           _ptr(wire_codes), _ptr(wire_scales), _stream()), "equarx_reduce_quantized")
+
+
+STATIC_WORKSPACE_BYTES = 80 << 20
+
+
+def equarx_reduce_quantized_static(partials, block: int, out_bf16) -> None:
+    """equarx_reduce_quantized with the wire buffers in the library's static device array (allocates nothing)."""
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+        if p.numel() != n:
+            raise ValueError("partials differ in length")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    _check(load().equarx_reduce_quantized_static(table, P, n, block, _ptr(out_bf16), _stream()),
+           "equarx_reduce_quantized_static")
 
 
 def equarx_reduce_quantized_fused_ends(partials, block: int, out_bf16, workspace=None) -> None:

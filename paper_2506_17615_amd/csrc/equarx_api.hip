@@ -2,14 +2,44 @@
 // The C ABI is declared and documented in include/equarx.h.
 #include "equarx.h"
 
+#include <atomic>
+
 #include "equarx_device.hpp"
 #include "equarx_launch.hpp"
 #include "equarx_strided.hpp"
+
+// Wire buffers of equarx_reduce_quantized_static, for callers that cannot allocate: one array per GPU, created
+// when the library's code object is loaded on that GPU and held until the process ends.  In host code this name
+// is only a handle for hipGetSymbolAddress -- never a device address.
+static __device__ __align__(256) unsigned char scratch[EQUARX_STATIC_WORKSPACE_BYTES];
 
 namespace {
 
 using namespace equarx;
 using namespace equarx::host;
+
+// The device address of `scratch` on each GPU, resolved on the first call made with that GPU current.
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char *> g_scratch_on_device[kMaxDevices];
+
+// EQUARX_OK and the current device's copy of `scratch`, or EQUARX_DEVICE_ERROR.
+int static_scratch(unsigned char **ptr)
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return EQUARX_DEVICE_ERROR;
+    unsigned char *p = g_scratch_on_device[device].load(std::memory_order_acquire);
+    if (!p) {
+        void *resolved = nullptr;
+        if (hipGetSymbolAddress(&resolved, HIP_SYMBOL(scratch)) != hipSuccess || !resolved) {
+            (void)hipGetLastError();
+            return EQUARX_DEVICE_ERROR;
+        }
+        p = static_cast<unsigned char *>(resolved);     // two threads racing here resolve the same address
+        g_scratch_on_device[device].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return EQUARX_OK;
+}
 
 template <int B>
 void launch_quantize(const uint16_t *x, int64_t n, int8_t *codes, float *scales, LaunchCtx &ctx)
@@ -516,6 +546,34 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
         s_prev = s_next;
     }
     do_dequantize(c_prev, s_prev, n, block, out_bf16, ctx);
+    return ctx.status();
+}
+
+int equarx_reduce_quantized_static(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
+                                   void *out_bf16, void *stream)
+{
+    LaunchCtx ctx(stream);
+    if (int st = check_shape(n, block)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
+    if (equarx_workspace_bytes(P, n, block) > (size_t)EQUARX_STATIC_WORKSPACE_BYTES) return EQUARX_WORKSPACE_TOO_SMALL;
+    Aliasing mem;
+    if (int st = check_partials(partials_bf16, P, n, mem)) return st;
+    mem.writes(out_bf16, (size_t)n * 2, kInPlace);
+    if (int st = mem.verdict()) return st;
+    unsigned char *wire = nullptr;
+    if (int st = static_scratch(&wire)) return st;
+    // Nothing in the array has to start at zero: pass 0 writes wire buffer 0 completely before hop 1 reads it,
+    // and every later hop reads only what the launch before it wrote.
+    const WireBuffers w = carve_workspace(wire, n, blocks_of(n, block));
+    do_quantize(partials_bf16[0], n, block, w.c[0], w.s[0], ctx);
+    for (int32_t i = 1; i < P; ++i) {
+        do_hop(w.c[(i - 1) & 1], w.s[(i - 1) & 1], partials_bf16[i], n, block, w.c[i & 1], w.s[i & 1], ctx);
+    }
+    do_dequantize(w.c[(P - 1) & 1], w.s[(P - 1) & 1], n, block, out_bf16, ctx);
     return ctx.status();
 }
 
