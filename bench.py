@@ -3,9 +3,19 @@
 
 A step is one pass of the whole hot path -- quantize, P-1 fused dequantize-add-requantize hops, final
 dequantize (equarx_reduce_quantized) -- over one batch of synthetic partial sums already resident in HBM.
-Prints ONE JSON line: effective input GB/s (bf16 bytes reduced per second), the roofline of the dominant
-kernel (the hop) from HIP events recorded around runs of hops inside the real call, the other schedules with
-their own byte counts, and the CPU oracle timed on the host as a reported baseline.
+Prints ONE JSON line:
+
+  value      effective input GB/s (bf16 bytes reduced per second): 2*P*n / (mean wall-clock time of a step over
+             the K timed steps, between two device synchronisations).  Inputs are COLD (two resident input sets
+             used in turn, more than the 256 MB Infinity Cache); the wire is WARM (each hop reads what the launch
+             before it wrote, which that cache still holds).
+  roofline   the dominant kernel (the hop), its duration measured with HIP events recorded on the stream around
+             runs of hops inside the real call.  `achieved`/`frac` are the warm-wire figures of the timed chain;
+             `cold_wire` holds the same kernel's figures when every wire it reads was written several launches
+             earlier (independent chains interleaved pass by pass), which is what a wire arriving from another
+             device looks like.
+  chain, other_schedules   every schedule with its own byte count, wall-clock figures and kernel figures kept apart.
+  cpu_baseline   the CPU oracle timed on the host as a reported baseline.
 """
 from __future__ import annotations
 
@@ -21,6 +31,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published peak
+INFINITY_CACHE_BYTES = 256 << 20
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hop_kernel_c3_traffic.txt")
 
 
@@ -39,26 +50,67 @@ def fused_bytes(P: int, n: int) -> float:
     return n * (2.0 * P + 2.0)
 
 
-def read_traffic():
-    """HBM bytes per hop launch from the committed rocprofv3 counter summary, or None."""
+def ends_bytes(P: int, n: int, block: int) -> float:
+    """Hop by hop with both ends fused: P-2 wire buffers written once and read once."""
+    return fused_bytes(P, n) + 2.0 * max(P - 2, 0) * n * (1.0 + 4.0 / block)
+
+
+def wire_bytes(n: int, block: int) -> float:
+    """Bytes of one wire buffer: int8 codes and fp32 scales."""
+    return n * (1.0 + 4.0 / block)
+
+
+def cold_chains(n: int, block: int) -> int:
+    """Independent chains to interleave so that a wire is cold when it is read: between its write and its read
+    the other chains write M-1 wires of their own, and those ALONE exceed the 256 MB Infinity Cache by a quarter
+    (counting only wire writes makes the arrangement safe whatever that cache does with the streamed bf16 inputs).
+    0 if that takes more than 64 chains (small messages: nothing about them is ever cold; no figure is reported)."""
+    m = int(-(-1.25 * INFINITY_CACHE_BYTES // wire_bytes(n, block))) + 1
+    return m if m <= 64 else 0
+
+
+def read_traffic(library_digest: str):
+    """Bytes per hop launch between L2 and the memory fabric, from the committed rocprofv3 counter summary, if that
+    summary was made with the library as it is built now; else None.  A profile, not a live measurement."""
     try:
         vals = {}
         with open(TRAFFIC_FILE) as f:
             for line in f:
-                if line.startswith("hbm_bytes_per_launch"):
-                    vals["t"] = float(line.split()[1])
-        return vals.get("t")
+                parts = line.split()
+                if len(parts) >= 2 and parts[0] in ("hbm_bytes_per_launch", "l2_fabric_bytes_per_launch"):
+                    vals["bytes"] = float(parts[1])
+                if len(parts) >= 2 and parts[0] == "library_digest":
+                    vals["digest"] = parts[1]
+        if "bytes" not in vals:
+            return None
+        if vals.get("digest") != library_digest:
+            return None
+        return vals["bytes"]
     except OSError:
         return None
 
 
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(w, host_u16, budget_s: float):
-    """The oracle as it stands, timed on this machine's host cores on the same workload (all cores, then one)."""
+    """The oracle as it stands, timed on this machine's host cores on the same workload: on as many threads as the box
+    grants (its OMP_NUM_THREADS share, else every CPU it shows), then on one."""
     import numpy as np
 
     from oracle import equarx_oracle as orc
     orc.build()
-    threads = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16") or 16)))
+    shown = os.cpu_count() or 1
+    granted = int(os.environ.get("OMP_NUM_THREADS", "0") or 0)
+    threads = max(1, min(shown, granted)) if granted > 0 else shown
 
     def timed(nthreads, budget, most):
         orc.set_threads(nthreads)
@@ -83,6 +135,9 @@ def cpu_baseline(w, host_u16, budget_s: float):
         "cores": used,
         "kind": "oracle",
         "sample": f"whole workload ({w.P} x {w.n} bf16), median of {reps} full chains, {best * 1e3:.0f} ms each",
+        "cpu_model": cpu_model(),
+        "host_cpus_shown": shown,
+        "threads_granted_by_OMP_NUM_THREADS": granted or None,
         "single_thread_value": round(2.0 * w.P * w.n / one / 1e9, 4),
         "single_thread_sample": f"median of {reps1} full chains, {one * 1e3:.0f} ms each",
         "rel_l2_vs_exact_sum": rel,
@@ -92,16 +147,20 @@ def cpu_baseline(w, host_u16, budget_s: float):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c3_gemma3_27b")
     ap.add_argument("--block", type=int, default=0, help="override the workload's block size")
     ap.add_argument("--rows", type=int, default=0,
                     help="override the workload's row count (e.g. rows/8: the share of one GPU of an 8-GPU node)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing; 0 skips it")
-    ap.add_argument("--schedule", choices=("hop", "fused"), default="hop",
-                    help="hop: P+1 launches, the wire written and read back (default, the schedule a ring imposes); "
-                         "fused: the same chain in one launch (equarx_reduce_fused)")
+    ap.add_argument("--schedule", choices=("hop", "ends", "fused"), default="hop",
+                    help="which schedule `value` reports.  hop: P+1 launches, the wire written and read back (default, "
+                         "the schedule a ring imposes); ends: the same with the first two and the last two passes "
+                         "sharing a launch; fused: the chain in one launch")
+    ap.add_argument("--only", choices=("all", "chain", "cold"), default="all",
+                    help="chain: run nothing but the timed steps of --schedule (for a clean kernel trace); "
+                         "cold: nothing but the interleaved cold-wire chains")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all P partials live in one MI355X's HBM); "
@@ -111,9 +170,9 @@ def main() -> int:
     import torch
 
     from paper_2506_17615_amd import binding as eq
+    from paper_2506_17615_amd import build as hip_build
     from paper_2506_17615_amd import workloads as wl
 
-    from paper_2506_17615_amd import build as hip_build
     hip_build.ensure_built()
     eq.load()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
@@ -124,6 +183,7 @@ def main() -> int:
         w = w.with_rows(args.rows)
     K, W = args.steps, args.warmup
     P, n, B = w.P, w.n, w.block
+    everything = args.only == "all"
 
     host = wl.make_partials(w)
     # two resident input sets, used in turn, so that no step finds its inputs in the 256 MB Infinity Cache
@@ -133,133 +193,25 @@ def main() -> int:
     work = eq.alloc_workspace(P, n, B)
     nb = eq.num_blocks(n, B)
 
+    def gbps(nbytes, ms):
+        return nbytes / (ms * 1e-3) / 1e9
+
+    def frac(nbytes, ms):
+        return round(gbps(nbytes, ms) / HBM_PEAK_GBPS, 4)
+
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        for k in range(W):
-            eq.equarx_reduce_quantized(sets[k % 2], B, out, work)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(K):
-            eq.equarx_reduce_quantized(sets[k % 2], B, out, work)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        hop_ms_per_step = (t1 - t0) * 1e3 / K
 
-        # spread of single steps: the same K steps once more, each between two events on the stream (the records
-        # themselves cost a microsecond or two per step, so the median sits slightly above ms_per_step)
-        marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
-        marks[0].record(stream)
-        for k in range(K):
-            eq.equarx_reduce_quantized(sets[k % 2], B, out, work)
-            marks[k + 1].record(stream)
-        torch.cuda.synchronize()
-        step_us = sorted(marks[k].elapsed_time(marks[k + 1]) * 1e3 for k in range(K))
-        spread = {"p10": round(step_us[int(0.1 * (K - 1))], 2), "median": round(step_us[(K - 1) // 2], 2),
-                  "p90": round(step_us[int(0.9 * (K - 1))], 2)}
-
-        # hop by hop with the first two and the last two passes sharing a launch: same bits, P-1 launches
-        for k in range(W):
-            eq.equarx_reduce_quantized_fused_ends(sets[k % 2], B, out, work)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(K):
-            eq.equarx_reduce_quantized_fused_ends(sets[k % 2], B, out, work)
-        torch.cuda.synchronize()
-        ends_ms_per_step = (time.perf_counter() - t0) * 1e3 / K
-        out_ends = out.clone()
-
-        # the same chain in one launch: same bits, no wire traffic
-        for k in range(W):
-            eq.equarx_reduce_fused(sets[k % 2], B, out)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(K):
-            eq.equarx_reduce_fused(sets[k % 2], B, out)
-        torch.cuda.synchronize()
-        fused_ms_per_step = (time.perf_counter() - t0) * 1e3 / K
-        fused_pairs = []
-        for _ in range(min(K, 50)):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            b.record(stream)
-            fused_pairs.append((a, b))
-        torch.cuda.synchronize()
-        for k, (a, b) in enumerate(fused_pairs):
-            eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
-            eq.equarx_reduce_fused(sets[k % 2], B, out)
-        torch.cuda.synchronize()
-        fused_kernel_ms = statistics.fmean(a.elapsed_time(b) for a, b in fused_pairs)
-        out_fused = out.clone()
-
-        # all-to-all form: every non-owner quantizes its shard once, the owner reduces all of them in one kernel
-        flat_info = None
-        if P > 1:
-            qc = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(P - 1)]
-            qs = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(P - 1)]
-
-            def flat_pipeline(parts):
-                eq.equarx_quantize_batch(parts[1:], B, qc, qs)
-                eq.equarx_reduce_flat(parts[0], qc, qs, B, out)
-
+        def timed_steps(call):
+            """W untimed calls, then exactly K between two synchronisations: mean wall-clock ms per step."""
             for k in range(W):
-                flat_pipeline(sets[k % 2])
+                call(k)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for k in range(K):
-                flat_pipeline(sets[k % 2])
+                call(k)
             torch.cuda.synchronize()
-            flat_ms = (time.perf_counter() - t0) * 1e3 / K
-            fp = []
-            for _ in range(min(K, 50)):
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(stream)
-                b.record(stream)
-                fp.append((a, b))
-            torch.cuda.synchronize()
-            for k, (a, b) in enumerate(fp):
-                eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
-                eq.equarx_reduce_flat(sets[k % 2][0], qc, qs, B, out)
-            torch.cuda.synchronize()
-            flat_kernel_ms = statistics.fmean(a.elapsed_time(b) for a, b in fp)
-            flat_kernel_bytes = n * (2.0 + (P - 1) * (1.0 + 4.0 / B) + 2.0)
-            flat_pipe_bytes = flat_kernel_bytes + (P - 1) * n * (2.0 + 1.0 + 4.0 / B)
-            ref = torch.zeros(n, dtype=torch.float64, device="cuda")
-            flat_pipeline(sets[0])
-            for p in sets[0]:
-                ref += p.double()
-            flat_rel = float((out.double() - ref).norm() / ref.norm())
-            del ref
-            flat_info = {
-                "schedule": "all-to-all form: one batched quantize of the P-1 sent shards, then one flat reduce + requantize kernel",
-                "ms_per_step": round(flat_ms, 5),
-                "effective_input_GBps": round(2.0 * P * n / (flat_ms * 1e-3) / 1e9, 1),
-                "algorithmic_bytes": flat_pipe_bytes,
-                "frac_of_hbm_peak": round(flat_pipe_bytes / (flat_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                "flat_kernel_avg_launch_us": round(flat_kernel_ms * 1e3, 3),
-                "flat_kernel_frac_of_hbm_peak": round(flat_kernel_bytes / (flat_kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                "rel_l2_vs_exact_sum": flat_rel,
-            }
-
-        # error of the result against the exact sum (fp64), computed with torch on the GPU
-        eq.equarx_reduce_fused(sets[0], B, out_fused)
-        eq.equarx_reduce_quantized(sets[0], B, out, work)
-        torch.cuda.synchronize()
-        assert torch.equal(out.view(torch.int16), out_fused.view(torch.int16)), "schedules disagree"
-        assert torch.equal(out.view(torch.int16), out_ends.view(torch.int16)), "schedules disagree"
-        ref = torch.zeros(n, dtype=torch.float64, device="cuda")
-        for p in sets[0]:
-            ref += p.double()
-        diff = out.double() - ref
-        rel_l2 = float(diff.norm() / ref.norm())
-        mse = float((diff * diff).mean())
-        max_abs = float(diff.abs().max())
-        del ref, diff
-
-        # the same K steps once more, each call with a pair of HIP events recorded on the stream around its hops
-        # (launches 1..P-1 of the call): the dominant kernel's duration inside the real chain, back to back as it
-        # runs there, nothing attached to the kernels themselves
-        codes = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(2)]
-        scales = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(2)]
+            return (time.perf_counter() - t0) * 1e3 / K
 
         def event_pairs(count):
             made = []
@@ -271,90 +223,268 @@ def main() -> int:
             torch.cuda.synchronize()
             return made
 
-        def per_launch_ms(call, first, count):
-            """Mean duration of one of `count` consecutive launches (from launch `first`) of call(k).  Spans of two
-            lengths are timed on alternate steps and subtracted, which cancels what the two event records cost."""
-            short = count // 2 if count >= 3 and K >= 4 else 0
-            pairs = event_pairs(K)
+        def per_launch_ms(call, first, count, group=1, reps=None):
+            """Mean duration of one of `count * group` consecutive launches (from launch `first`) of call(k).  Spans of
+            two lengths are timed on alternate calls and subtracted, which cancels what the two event records cost."""
+            reps = reps or K
+            short = count // 2 if count >= 3 and reps >= 4 else 0
+            for k in range(min(W, 10)):     # untimed: first touches of fresh buffers, clocks
+                call(k)
+            pairs = event_pairs(reps)
             for k, (a, b) in enumerate(pairs):
                 length = short if (short and k % 2) else count
-                eq.equarx_time_launch_span(first, first + length - 1, a.cuda_event, b.cuda_event)
+                eq.equarx_time_launch_span(first, first + length * group - 1, a.cuda_event, b.cuda_event)
                 call(k)
             torch.cuda.synchronize()
             times = [a.elapsed_time(b) for a, b in pairs]
             if not short:
-                return statistics.fmean(times) / count, len(times) * count
+                return statistics.fmean(times) / (count * group), len(times) * count * group
             long_ms, short_ms = statistics.fmean(times[0::2]), statistics.fmean(times[1::2])
-            return (long_ms - short_ms) / (count - short), len(times[0::2]) * count + len(times[1::2]) * short
+            return ((long_ms - short_ms) / ((count - short) * group),
+                    (len(times[0::2]) * count + len(times[1::2]) * short) * group)
 
-        kernel_ms, launches_timed = per_launch_ms(lambda k: eq.equarx_reduce_quantized(sets[k % 2], B, out, work),
-                                                  1 if P > 1 else 0, max(P - 1, 1))
-
-        # calibration: the hops' loads and stores without their arithmetic, same ping-pong, same cadence
-        traffic_only_ms = None
-        if P > 1 and n % B == 0:
-            traffic_only_ms, _ = per_launch_ms(
-                lambda k: eq.equarx_calib_hop_traffic(sets[k % 2], B, codes[0], scales[0], codes[1], scales[1]),
-                0, P - 1)
-
-        # calibration: what a plain 16-byte copy reaches on this device over the same footprint
-        src = torch.empty(2 * P * n // 2, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            eq.equarx_calib_copy(src, dst)
-        cp = []
-        for _ in range(10):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            b.record(stream)
+        def single_kernel_ms(call, reps):
+            """Mean duration of the one kernel call(k) launches, from an event pair the launch itself carries."""
+            pairs = event_pairs(reps)
+            for k, (a, b) in enumerate(pairs):
+                eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
+                call(k)
             torch.cuda.synchronize()
-            eq.equarx_time_next_launch(a.cuda_event, b.cuda_event)
-            eq.equarx_calib_copy(src, dst)
+            return statistics.fmean(a.elapsed_time(b) for a, b in pairs)
+
+        calls = {
+            "hop": lambda k: eq.equarx_reduce_quantized(sets[k % 2], B, out, work),
+            "ends": lambda k: eq.equarx_reduce_quantized_fused_ends(sets[k % 2], B, out, work),
+            "fused": lambda k: eq.equarx_reduce_fused(sets[k % 2], B, out),
+        }
+        descriptions = {
+            "hop": "hop-by-hop, P+1 launches, wire written once and read once",
+            "ends": "hop-by-hop with both ends fused: max(P-1, 1) launches, P-2 wire buffers written once and read once",
+            "fused": "single launch, chain in registers, no wire traffic",
+        }
+        own_bytes = {"hop": chain_bytes(P, n, B), "ends": ends_bytes(P, n, B), "fused": fused_bytes(P, n)}
+
+        infos = {}
+        results = {}
+        wanted = list(calls) if everything else ([args.schedule] if args.only == "chain" else [])
+        for name in wanted:
+            ms = timed_steps(calls[name])
+            results[name] = out.clone()
+            infos[name] = {
+                "schedule": descriptions[name],
+                "ms_per_step": round(ms, 5),
+                "effective_input_GBps": round(gbps(2.0 * P * n, ms), 1),
+                "algorithmic_bytes": own_bytes[name],
+                "frac_of_hbm_peak": frac(own_bytes[name], ms),
+                "inputs": "cold (two input sets in turn)",
+                "wire": "none" if name == "fused" else "warm (read by the launch after the one that wrote it)",
+            }
+        if "hop" in infos:
+            # spread of single steps: the same K steps once more, each between two events on the stream (the records
+            # themselves cost a microsecond or two per step, so the median sits slightly above ms_per_step)
+            marks = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+            marks[0].record(stream)
+            for k in range(K):
+                calls["hop"](k)
+                marks[k + 1].record(stream)
             torch.cuda.synchronize()
-            cp.append(a.elapsed_time(b))
-        copy_gbps = 2.0 * src.numel() / (statistics.median(cp) * 1e-3) / 1e9
+            step_us = sorted(marks[k].elapsed_time(marks[k + 1]) * 1e3 for k in range(K))
+            infos["hop"]["single_step_us"] = {"p10": round(step_us[int(0.1 * (K - 1))], 2),
+                                              "median": round(step_us[(K - 1) // 2], 2),
+                                              "p90": round(step_us[int(0.9 * (K - 1))], 2)}
+        if "fused" in infos and everything:
+            kms = single_kernel_ms(calls["fused"], min(K, 50))
+            infos["fused"]["kernel_avg_launch_us"] = round(kms * 1e3, 3)
+            infos["fused"]["kernel_frac_of_hbm_peak"] = frac(fused_bytes(P, n), kms)
 
-    def gbps(nbytes, ms):
-        return nbytes / (ms * 1e-3) / 1e9
+        # all-to-all form: every non-owner quantizes its shard once, the owner reduces all of them in one kernel
+        flat_info = None
+        if P > 1 and everything:
+            qc = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(P - 1)]
+            qs = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(P - 1)]
 
-    hop_info = {
-        "schedule": "hop-by-hop, P+1 launches, wire written once and read once",
-        "ms_per_step": round(hop_ms_per_step, 5),
-        "effective_input_GBps": round(gbps(2.0 * P * n, hop_ms_per_step), 1),
-        "algorithmic_bytes": chain_bytes(P, n, B),
-        "frac_of_hbm_peak": round(gbps(chain_bytes(P, n, B), hop_ms_per_step) / HBM_PEAK_GBPS, 4),
-        "single_step_us": spread,
-    }
-    fused_info = {
-        "schedule": "single launch, chain in registers, no wire traffic",
-        "ms_per_step": round(fused_ms_per_step, 5),
-        "effective_input_GBps": round(gbps(2.0 * P * n, fused_ms_per_step), 1),
-        "algorithmic_bytes": fused_bytes(P, n),
-        "frac_of_hbm_peak": round(gbps(fused_bytes(P, n), fused_ms_per_step) / HBM_PEAK_GBPS, 4),
-        "kernel_avg_launch_us": round(fused_kernel_ms * 1e3, 3),
-    }
-    ends_bytes = fused_bytes(P, n) + 2.0 * max(P - 2, 0) * n * (1.0 + 4.0 / B)
-    ends_info = {
-        "schedule": "hop-by-hop with both ends fused: max(P-1, 1) launches, P-2 wire buffers written once and read once",
-        "ms_per_step": round(ends_ms_per_step, 5),
-        "effective_input_GBps": round(gbps(2.0 * P * n, ends_ms_per_step), 1),
-        "algorithmic_bytes": ends_bytes,
-        "frac_of_hbm_peak": round(gbps(ends_bytes, ends_ms_per_step) / HBM_PEAK_GBPS, 4),
-    }
-    if args.schedule == "hop":
-        ms_per_step, chosen, other = hop_ms_per_step, hop_info, fused_info
-        dominant = "hop (dequantize + fp32 add + requantize)" if P > 1 else "quantize"
-        per_launch = hop_bytes(n, B) if P > 1 else n * (2.0 + 1.0 + 4.0 / B)
-        traffic = read_traffic() if (w.name, B) == ("c3_gemma3_27b", 256) else None
-    else:
-        ms_per_step, chosen, other = fused_ms_per_step, fused_info, hop_info
+            def flat_pipeline(k):
+                eq.equarx_quantize_batch(sets[k % 2][1:], B, qc, qs)
+                eq.equarx_reduce_flat(sets[k % 2][0], qc, qs, B, out)
+
+            flat_ms = timed_steps(flat_pipeline)
+            flat_kernel_ms = single_kernel_ms(lambda k: eq.equarx_reduce_flat(sets[k % 2][0], qc, qs, B, out), min(K, 50))
+            flat_kernel_bytes = n * (2.0 + (P - 1) * (1.0 + 4.0 / B) + 2.0)
+            flat_pipe_bytes = flat_kernel_bytes + (P - 1) * n * (2.0 + 1.0 + 4.0 / B)
+            ref = torch.zeros(n, dtype=torch.float64, device="cuda")
+            flat_pipeline(0)
+            for p in sets[0]:
+                ref += p.double()
+            flat_rel = float((out.double() - ref).norm() / ref.norm())
+            del ref, qc, qs
+            flat_info = {
+                "schedule": "all-to-all form: one batched quantize of the P-1 sent shards, then one flat reduce + requantize kernel",
+                "ms_per_step": round(flat_ms, 5),
+                "effective_input_GBps": round(gbps(2.0 * P * n, flat_ms), 1),
+                "algorithmic_bytes": flat_pipe_bytes,
+                "frac_of_hbm_peak": frac(flat_pipe_bytes, flat_ms),
+                "flat_kernel_avg_launch_us": round(flat_kernel_ms * 1e3, 3),
+                "flat_kernel_frac_of_hbm_peak": frac(flat_kernel_bytes, flat_kernel_ms),
+                "rel_l2_vs_exact_sum": flat_rel,
+            }
+
+        # error of the result against the exact sum (fp64), computed with torch on the GPU; all schedules agree bit for bit
+        rel_l2 = mse = max_abs = None
+        if everything:
+            calls["hop"](0)
+            torch.cuda.synchronize()
+            first = out.clone()
+            for name, got in results.items():
+                calls[name](0)
+                torch.cuda.synchronize()
+                assert torch.equal(out.view(torch.int16), first.view(torch.int16)), f"schedule {name} disagrees"
+            ref = torch.zeros(n, dtype=torch.float64, device="cuda")
+            for p in sets[0]:
+                ref += p.double()
+            diff = first.double() - ref
+            rel_l2 = float(diff.norm() / ref.norm())
+            mse = float((diff * diff).mean())
+            max_abs = float(diff.abs().max())
+            del ref, diff, first
+        results.clear()
+
+        # the dominant kernel inside the real chain: events recorded on the stream around its hops (launches 1..P-1 of
+        # the call), back to back as they run there, nothing attached to the kernels themselves
+        kernel_ms = launches_timed = traffic_only_ms = copy_gbps = None
+        if everything and P > 1:
+            kernel_ms, launches_timed = per_launch_ms(calls["hop"], 1, P - 1)
+            if n % B == 0:      # calibration: the hops' loads and stores without their arithmetic, same ping-pong, same cadence
+                codes = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(2)]
+                scales = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(2)]
+                traffic_only_ms, _ = per_launch_ms(
+                    lambda k: eq.equarx_calib_hop_traffic(sets[k % 2], B, codes[0], scales[0], codes[1], scales[1]),
+                    0, P - 1)
+                del codes, scales
+        elif everything:
+            kernel_ms, launches_timed = per_launch_ms(calls["hop"], 0, 1)
+        empty_us = None
+        if everything:      # calibration: the stream time of a launch that does nothing, at the hop kernel's grid size
+            grid = -(-n // (2048 * 3))
+            for _ in range(3):
+                eq.equarx_calib_empty_launches(64, grid)
+            ev = event_pairs(10)
+            for a, b in ev:
+                a.record(stream)
+                eq.equarx_calib_empty_launches(256, grid)
+                b.record(stream)
+            torch.cuda.synchronize()
+            empty_us = statistics.median(a.elapsed_time(b) for a, b in ev) * 1e3 / 256
+        if everything:      # calibration: what a plain 16-byte copy reaches on this device over the same footprint
+            src = torch.empty(2 * P * n // 2, dtype=torch.uint8, device="cuda")
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                eq.equarx_calib_copy(src, dst)
+            copy_ms = single_kernel_ms(lambda k: eq.equarx_calib_copy(src, dst), 10)
+            copy_gbps = 2.0 * src.numel() / (copy_ms * 1e-3) / 1e9
+            del src, dst
+
+        # cold wire: M independent chains interleaved pass by pass, every wire read M-1 launches after it was written
+        cold = None
+        M = cold_chains(n, B) if P > 1 and args.only in ("all", "cold") else 0
+        if M:
+            more = [sets[0], sets[1]] + [[p.clone() for p in sets[0]] for _ in range(M - 2)]
+            more = more[:M]
+            outs = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(M)]
+            works = [eq.alloc_workspace(P, n, B) for _ in range(M)]
+            rounds = max(2, -(-K // M))
+
+            def cold_ms(streaming):
+                for _ in range(2):
+                    eq.equarx_calib_interleaved_chains(more, B, outs, works, streaming)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(rounds):
+                    eq.equarx_calib_interleaved_chains(more, B, outs, works, streaming)
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) * 1e3 / (rounds * M)
+
+            # hops are launches M .. P*M-1 of the call: (P-1) groups of M launches, all of them cold-wire hops
+            def cold_hop(streaming):
+                return per_launch_ms(lambda k: eq.equarx_calib_interleaved_chains(more, B, outs, works, streaming),
+                                     M, P - 1, group=M, reps=max(4, 2 * rounds))
+
+            stream_ms = cold_ms(True)
+            stream_hop_ms, cold_launches = cold_hop(True)
+            # the same arrangement with the chain entry points' cacheable wire accesses: only with --only cold, so that
+            # in the default run each kernel symbol stands for one situation (hop_kernel<.., false>: warm wire inside
+            # the timed chain; hop_kernel<.., true>: cold wire) and a kernel trace of the run can be read directly
+            cached_ms = cached_hop_ms = None
+            if args.only == "cold":
+                cached_ms = cold_ms(False)
+                cached_hop_ms, _ = cold_hop(False)
+            calls["hop"](0)
+            torch.cuda.synchronize()
+            assert all(torch.equal(o.view(torch.int16), out.view(torch.int16)) for o in outs), "cold chains disagree"
+            cold = {
+                "how": f"{M} independent chains interleaved pass by pass: every wire is read {M - 1} launches after it was "
+                       f"written, behind {(M - 1) * wire_bytes(n, B) / 1e6:.0f} MB of other wires written and "
+                       f"{(M - 1) * hop_bytes(n, B) / 1e6:.0f} MB of traffic in all; inputs cold as well; wire accessed "
+                       f"with non-temporal hints, as the per-step entry points (equarx_quantize, equarx_reduce_stage, "
+                       f"equarx_dequantize) access it",
+                "chains_interleaved": M,
+                "ms_per_step": round(stream_ms, 5),
+                "effective_input_GBps": round(gbps(2.0 * P * n, stream_ms), 1),
+                "frac_of_hbm_peak": frac(chain_bytes(P, n, B), stream_ms),
+                "cacheable_wire_ms_per_step": round(cached_ms, 5) if cached_ms else None,
+                "cacheable_wire_frac_of_hbm_peak": frac(chain_bytes(P, n, B), cached_ms) if cached_ms else None,
+                "hop_kernel_us": round(stream_hop_ms * 1e3, 3),
+                "hop_kernel_frac_of_hbm_peak": frac(hop_bytes(n, B), stream_hop_ms),
+                "hop_kernel_cacheable_wire_us": round(cached_hop_ms * 1e3, 3) if cached_hop_ms else None,
+                "hop_launches_timed": cold_launches,
+            }
+            del more, outs, works
+
+    chosen = infos.get(args.schedule)
+    if chosen is None:          # --only cold
+        print(json.dumps({"config": {"workload": w.name, "P": P, "n": n, "block": B}, "cold_wire": cold}), flush=True)
+        return 0
+    ms_per_step = chosen["ms_per_step"]
+    value = 2.0 * P * n / (ms_per_step * 1e-3) / 1e9
+    if args.schedule == "fused":
         dominant = "chain (all hops in one launch)"
         per_launch = fused_bytes(P, n)
-        kernel_ms, launches_timed = fused_kernel_ms, len(fused_pairs)
-        traffic = None
-    achieved = per_launch / (kernel_ms * 1e-3) / 1e9
-    value = 2.0 * P * n / (ms_per_step * 1e-3) / 1e9
+        kernel_ms = (chosen.get("kernel_avg_launch_us") or 0) * 1e-3 or None
+        launches_timed = min(K, 50) if kernel_ms else None
+    else:
+        dominant = "hop (dequantize + fp32 add + requantize)" if P > 1 else "quantize"
+        per_launch = hop_bytes(n, B) if P > 1 else n * (2.0 + 1.0 + 4.0 / B)
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": None, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": None,
+                "traffic": None, "bytes_per_launch": per_launch}
+    if kernel_ms:
+        achieved = per_launch / (kernel_ms * 1e-3) / 1e9
+        roofline.update({
+            "achieved": round(achieved, 1), "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "avg_launch_us": round(kernel_ms * 1e3, 3), "launches_timed": launches_timed,
+            "measured": "HIP events on the stream around runs of this kernel inside the timed entry point; inputs cold, "
+                        "wire warm (written by the previous launch, still in the 256 MB Infinity Cache)",
+        })
+    if args.schedule != "fused":
+        traffic = read_traffic(hip_build.source_digest()) if (w.name, B) == ("c3_gemma3_27b", 256) else None
+        roofline.update({
+            "traffic": traffic,
+            "traffic_source": ("profiles/hop_kernel_c3_traffic.txt: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE per dispatch, "
+                               "each scaled by the same counter's reading for a copy of known size; a committed profile "
+                               "of this library build, not measured by this run") if traffic else None,
+            "traffic_level": "bytes between L2 and the memory fabric (Infinity Cache + HBM together; not DRAM bytes)",
+            "same_traffic_no_arithmetic_us": round(traffic_only_ms * 1e3, 3) if traffic_only_ms else None,
+            "cold_wire": ({"avg_launch_us": cold["hop_kernel_us"],
+                           "achieved": round(hop_bytes(n, B) / (cold["hop_kernel_us"] * 1e-6) / 1e9, 1),
+                           "frac": cold["hop_kernel_frac_of_hbm_peak"], "launches_timed": cold["hop_launches_timed"],
+                           "cacheable_wire_avg_launch_us": cold["hop_kernel_cacheable_wire_us"],
+                           "measured": cold["how"]} if cold else None),
+        })
+    if copy_gbps:
+        roofline["copy_kernel_GBps"] = round(copy_gbps, 1)
+    if empty_us:
+        roofline["empty_launch_pitch_us"] = round(empty_us, 3)
 
+    if cold:
+        chosen = dict(chosen, cold_wire={k: v for k, v in cold.items() if not k.startswith("hop_")})
     result = {
         "metric": "effective input GB/s (bf16 bytes reduced/sec)",
         "value": round(value, 2),
@@ -368,19 +498,15 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
+        "value_is": "mean over the K timed steps (wall clock between two device synchronisations); inputs cold, wire warm",
         "config": {"workload": w.name, "P": P, "rows": w.rows, "hidden": w.hidden, "n": n, "block": B,
                    "distribution": w.dist, "schedule": chosen["schedule"]},
         "chain": chosen,
-        "other_schedules": [x for x in (ends_info, other, flat_info) if x],
-        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "bytes_per_launch": per_launch, "avg_launch_us": round(kernel_ms * 1e3, 3),
-                     "launches_timed": launches_timed, "copy_kernel_GBps": round(copy_gbps, 1),
-                     "same_traffic_no_arithmetic_us": (round(traffic_only_ms * 1e3, 3)
-                                                       if traffic_only_ms and args.schedule == "hop" else None)},
+        "other_schedules": [v for k, v in infos.items() if k != args.schedule] + ([flat_info] if flat_info else []),
+        "roofline": roofline,
         "error_vs_exact_sum": {"rel_l2": rel_l2, "mse": mse, "max_abs": max_abs},
     }
-    if args.cpu_seconds > 0:
+    if args.cpu_seconds > 0 and everything:
         result["cpu_baseline"] = cpu_baseline(w, [wl.as_u16(p) for p in host], args.cpu_seconds)
     print(json.dumps(result), flush=True)
     return 0

@@ -33,6 +33,14 @@
  *   - Pointers must be 16-byte aligned (8-byte for codes, 4 for scales is not
  *     enough: every data pointer is checked against 16).
  *   - Supported block sizes: 32, 64, 128, 256, 512.
+ *   - equarx_quantize, equarx_reduce_stage and equarx_dequantize are the calls
+ *     one device of a ring makes per step: the wire they read arrived from
+ *     another device and the wire they write leaves for one, so they access
+ *     it with non-temporal hints (read once; not read here again).  The chain
+ *     entry points run every step on this device and keep the wire cacheable
+ *     for the next launch.  Same results either way; a chain composed by hand
+ *     from the per-step calls on one device is a few percent slower than
+ *     equarx_reduce_quantized.
  *   - NaN or infinite inputs give unspecified codes/scales but never a fault.
  */
 #ifndef EQUARX_H

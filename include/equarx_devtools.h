@@ -20,6 +20,12 @@ extern "C" {
  * find the HBM bandwidth a streaming kernel can reach on this device. */
 int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/* `count` launches (0 .. 4096), back to back on `stream`, of a kernel of
+ * `workgroups` 256-thread workgroups that does nothing: what a launch costs on
+ * this device before it moves a byte (the benchmark reports the pitch of such
+ * launches beside the kernels' durations). */
+int equarx_calib_empty_launches(int32_t count, int32_t workgroups, void *stream);
+
 /* The chain's hops as memory traffic only: P-1 launches of a kernel with
  * exactly the loads and stores of equarx_reduce_stage (same tiling, same
  * access widths, the same ping-pong between two wire buffers, partial i read by
@@ -32,6 +38,32 @@ int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
  * codes written = (X0^X2^C0, X1^X3^C1); scales written = scales read. */
 int equarx_calib_hop_traffic(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,
                              int8_t *codes0, float *scales0, int8_t *codes1, float *scales1, void *stream);
+
+/*
+ * M independent hop-by-hop reductions of the same shape, their launches
+ * interleaved pass by pass: pass 0 of chains 0 .. M-1, then pass 1 of chains
+ * 0 .. M-1, and so on (launch number pass * M + m).  Each chain is exactly
+ * equarx_reduce_quantized on its own inputs, workspace and output -- same
+ * kernels, same bits -- but every wire is read M-1 launches after it was
+ * written, so that with M large enough it no longer sits in a cache when the
+ * next hop reads it: the benchmark's stand-in for a wire that arrives from
+ * another device instead of from the previous launch.
+ *
+ *   partials_bf16   HOST array of M*P device pointers; chain m's partial i
+ *                   is entry m*P + i.
+ *   out_bf16        HOST array of M device pointers, bf16 [n] each; not in place.
+ *   workspaces      HOST array of M device pointers, each to workspace_bytes
+ *                   >= equarx_workspace_bytes(P, n, block) bytes, 256-byte aligned.
+ *   streaming       0: the wire is accessed as the chain entry points access
+ *                   it (cacheable); non-zero: as the per-step entry points do
+ *                   (non-temporal hints).
+ *   1 <= M <= EQUARX_CALIB_MAX_CHAINS.  No output or workspace may overlap
+ *   any other buffer of the call.
+ */
+#define EQUARX_CALIB_MAX_CHAINS 64
+int equarx_calib_interleaved_chains(const void *const *partials_bf16, int32_t M, int32_t P, int64_t n, int32_t block,
+                                    void *const *out_bf16, void *const *workspaces, size_t workspace_bytes,
+                                    int32_t streaming, void *stream);
 
 /*
  * Self-tests of the kernels' arithmetic (used by the test suite).

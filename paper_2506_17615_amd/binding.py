@@ -58,6 +58,9 @@ SIGNATURES = {
 DEVTOOLS_SIGNATURES = {
     "equarx_calib_hop_traffic": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _vp, _vp, _vp]),
     "equarx_calib_copy": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
+    "equarx_calib_empty_launches": (ctypes.c_int, [_i32, _i32, _vp]),
+    "equarx_calib_interleaved_chains": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i32, _i64, _i32, ctypes.POINTER(_vp),
+                                                       ctypes.POINTER(_vp), _sz, _i32, _vp]),
     "equarx_selftest_quotients": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint64, _vp, _vp]),
     "equarx_selftest_rounding": (ctypes.c_int, [ctypes.c_uint32, ctypes.c_uint64, _vp, _vp]),
     "equarx_eval_quotients": (ctypes.c_int, [_vp, _i64, _vp, _vp, _vp]),
@@ -392,6 +395,11 @@ def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     _check(load().equarx_calib_copy(_ptr(src), _ptr(dst), nbytes, _stream()), "equarx_calib_copy")
 
 
+def equarx_calib_empty_launches(count: int, workgroups: int) -> None:
+    """`count` back-to-back launches of a kernel that does nothing (`workgroups` workgroups each)."""
+    _check(load().equarx_calib_empty_launches(count, workgroups, _stream()), "equarx_calib_empty_launches")
+
+
 def equarx_calib_hop_traffic(partials, block: int, codes0, scales0, codes1, scales1) -> None:
     """The chain's P-1 hops as memory traffic only (XOR of what each launch read), ping-pong between two wires."""
     P = len(partials)
@@ -405,6 +413,31 @@ def equarx_calib_hop_traffic(partials, block: int, codes0, scales0, codes1, scal
     table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
     _check(load().equarx_calib_hop_traffic(table, P, n, block, _ptr(codes0), _ptr(scales0), _ptr(codes1),
                                            _ptr(scales1), _stream()), "equarx_calib_hop_traffic")
+
+
+def equarx_calib_interleaved_chains(partial_sets, block: int, outs, workspaces, streaming: bool = False) -> None:
+    """len(partial_sets) independent hop-by-hop chains, interleaved pass by pass (every wire read M-1 launches after
+    it was written); chain m reduces partial_sets[m] into outs[m] using workspaces[m].  streaming: the wire is
+    accessed with non-temporal hints, as the per-step entry points access it."""
+    M = len(partial_sets)
+    P = len(partial_sets[0]) if M else 0
+    n = partial_sets[0][0].numel() if P else 0
+    if len(outs) != M or len(workspaces) != M or any(len(ps) != P for ps in partial_sets):
+        raise ValueError("one output, one workspace and P partials per chain")
+    need = workspace_bytes(P, n, block) if P else 0
+    for ps, o, w in zip(partial_sets, outs, workspaces):
+        for p in ps:
+            _need(p, torch.bfloat16, n, "partial")
+            if p.numel() != n:
+                raise ValueError("partials differ in length")
+        _need(o, torch.bfloat16, n, "out_bf16")
+        _need(w, torch.uint8, need, "workspace")
+    flat = [p.data_ptr() for ps in partial_sets for p in ps]
+    ptab = (_vp * max(len(flat), 1))(*flat)
+    otab = (_vp * max(M, 1))(*[o.data_ptr() for o in outs])
+    wtab = (_vp * max(M, 1))(*[w.data_ptr() for w in workspaces])
+    _check(load().equarx_calib_interleaved_chains(ptab, M, P, n, block, otab, wtab, need, int(bool(streaming)), _stream()),
+           "equarx_calib_interleaved_chains")
 
 
 def equarx_time_launch_span(first: int, last: int, start_event, stop_event) -> None:

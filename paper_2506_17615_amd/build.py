@@ -10,7 +10,7 @@ CSRC = os.path.join(_PKG, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_PKG, "libequarx.so")
 SOURCES = [os.path.join(CSRC, "equarx_api.hip"), os.path.join(CSRC, "equarx_devtools.hip")]
-HEADERS = [os.path.join(CSRC, name) for name in ("equarx_device.hpp", "equarx_strided.hpp", "equarx_launch.hpp",
+HEADERS = [os.path.join(CSRC, name) for name in ("equarx_device.hpp", "equarx_strided.hpp", "equarx_launch.hpp", "equarx_passes.hpp",
                                                   "equarx_devtools_kernels.hpp")]
 HEADERS += [os.path.join(INCLUDE, "equarx.h"), os.path.join(INCLUDE, "equarx_devtools.h")]
 

@@ -6,6 +6,7 @@
 
 #include "equarx_device.hpp"
 #include "equarx_launch.hpp"
+#include "equarx_passes.hpp"
 #include "equarx_strided.hpp"
 
 // Wire buffers of equarx_reduce_quantized_static, for callers that cannot allocate: one array per GPU, created
@@ -39,26 +40,6 @@ int static_scratch(unsigned char **ptr)
     }
     *ptr = p;
     return EQUARX_OK;
-}
-
-template <int B>
-void launch_quantize(const uint16_t *x, int64_t n, int8_t *codes, float *scales, LaunchCtx &ctx)
-{
-    ctx.launch(quantize_kernel<B, kTilesQuantize>, grid_for(n, kTilesQuantize), kThreads, x, n, codes, scales, blocks_of(n, B));
-}
-
-template <int B>
-void launch_hop(const int8_t *cin, const float *sin, const uint16_t *x, int64_t n, int8_t *cout, float *sout,
-                LaunchCtx &ctx)
-{
-    ctx.launch(hop_kernel<B, kTilesHop>, grid_for(n, kTilesHop), kThreads, cin, sin, x, n, cout, sout, blocks_of(n, B));
-}
-
-template <int B>
-void launch_dequantize(const int8_t *codes, const float *scales, int64_t n, uint16_t *out, LaunchCtx &ctx)
-{
-    ctx.launch(dequantize_kernel<B, kTilesDequantize>, grid_for(n, kTilesDequantize), kThreads, codes, scales, n, out,
-           blocks_of(n, B));
 }
 
 template <int B>
@@ -234,6 +215,12 @@ void launch_flat(const uint16_t *local, const WireTable &tab, int R, int64_t n, 
     }
 }
 
+// The three per-step entry points (equarx_quantize, equarx_reduce_stage, equarx_dequantize) are what a device of a
+// ring calls once per step: the wire they read came from another device and the wire they write goes to one, so
+// they access it with non-temporal hints.  The chain entry points, which run every step on this device, know that
+// the next launch reads what this one wrote and keep the wire cacheable.
+constexpr bool kWireLeavesTheDevice = true;
+
 // The output of a chain may BE one of the partials (in-place reduction: every
 // kernel reads an element of every partial before the thread that owns the
 // element writes it, and in the hop-by-hop schedules the output is written by
@@ -279,38 +266,6 @@ inline WireBuffers carve_workspace(void *workspace, int64_t n, int64_t scales_co
         b.s[i] = reinterpret_cast<float *>(w + (size_t)i * (codes + scales) + codes);
     }
     return b;
-}
-
-#define EQUARX_DISPATCH_BLOCK(block, CALL)      \
-    switch (block) {                            \
-        case 32: CALL(32); break;               \
-        case 64: CALL(64); break;               \
-        case 128: CALL(128); break;             \
-        case 256: CALL(256); break;             \
-        case 512: CALL(512); break;             \
-        default: break;                         \
-    }
-
-void do_quantize(const void *x, int64_t n, int32_t block, int8_t *codes, float *scales, LaunchCtx &ctx)
-{
-#define CALL(BB) launch_quantize<BB>(static_cast<const uint16_t *>(x), n, codes, scales, ctx)
-    EQUARX_DISPATCH_BLOCK(block, CALL)
-#undef CALL
-}
-
-void do_hop(const int8_t *cin, const float *sin, const void *x, int64_t n, int32_t block, int8_t *cout, float *sout,
-            LaunchCtx &ctx)
-{
-#define CALL(BB) launch_hop<BB>(cin, sin, static_cast<const uint16_t *>(x), n, cout, sout, ctx)
-    EQUARX_DISPATCH_BLOCK(block, CALL)
-#undef CALL
-}
-
-void do_dequantize(const int8_t *codes, const float *scales, int64_t n, int32_t block, void *out, LaunchCtx &ctx)
-{
-#define CALL(BB) launch_dequantize<BB>(codes, scales, n, static_cast<uint16_t *>(out), ctx)
-    EQUARX_DISPATCH_BLOCK(block, CALL)
-#undef CALL
 }
 
 // ---- strided (Sec. 3.2) geometry ----
@@ -414,7 +369,7 @@ int equarx_quantize(const void *x_bf16, int64_t n, int32_t block, int8_t *codes,
     mem.writes(codes, (size_t)n);
     mem.writes(scales, (size_t)blocks_of(n, block) * sizeof(float));
     if (int st = mem.verdict()) return st;
-    do_quantize(x_bf16, n, block, codes, scales, ctx);
+    do_quantize(x_bf16, n, block, codes, scales, ctx, kWireLeavesTheDevice);
     return ctx.status();
 }
 
@@ -467,7 +422,7 @@ int equarx_dequantize(const int8_t *codes, const float *scales, int64_t n, int32
     mem.reads(scales, (size_t)blocks_of(n, block) * sizeof(float));
     mem.writes(out_bf16, (size_t)n * 2);
     if (int st = mem.verdict()) return st;
-    do_dequantize(codes, scales, n, block, out_bf16, ctx);
+    do_dequantize(codes, scales, n, block, out_bf16, ctx, kWireLeavesTheDevice);
     return ctx.status();
 }
 
@@ -496,7 +451,7 @@ int equarx_reduce_stage(const int8_t *codes_in, const float *scales_in, const vo
         misaligned(codes_out, kAlign) || misaligned(scales_out, kAlign))
         return EQUARX_MISALIGNED;
     if (int st = check_hop_memory(codes_in, scales_in, local_bf16, n, blocks_of(n, block), codes_out, scales_out)) return st;
-    do_hop(codes_in, scales_in, local_bf16, n, block, codes_out, scales_out, ctx);
+    do_hop(codes_in, scales_in, local_bf16, n, block, codes_out, scales_out, ctx, kWireLeavesTheDevice);
     return ctx.status();
 }
 

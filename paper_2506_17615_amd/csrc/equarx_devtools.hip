@@ -7,6 +7,7 @@
 
 #include "equarx_devtools_kernels.hpp"
 #include "equarx_launch.hpp"
+#include "equarx_passes.hpp"
 
 using namespace equarx;
 using namespace equarx::host;
@@ -28,6 +29,14 @@ int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream)
     const int64_t per_wg = kThreads * 4;
     ctx.launch(copy_kernel, (unsigned)((nvec + per_wg - 1) / per_wg), kThreads, static_cast<const u32x4 *>(src),
                static_cast<u32x4 *>(dst), nvec);
+    return ctx.status();
+}
+
+int equarx_calib_empty_launches(int32_t count, int32_t workgroups, void *stream)
+{
+    LaunchCtx ctx(stream);
+    if (count < 0 || count > 4096 || workgroups < 1 || workgroups > (1 << 20)) return EQUARX_BAD_SHAPE;
+    for (int32_t i = 0; i < count; ++i) ctx.launch(empty_kernel, (unsigned)workgroups, kThreads, 0);
     return ctx.status();
 }
 
@@ -72,6 +81,56 @@ int equarx_calib_hop_traffic(const void *const *partials_bf16, int32_t P, int64_
         default: break;
     }
 #undef CALL
+    return ctx.status();
+}
+
+int equarx_calib_interleaved_chains(const void *const *partials_bf16, int32_t M, int32_t P, int64_t n, int32_t block,
+                                    void *const *out_bf16, void *const *workspaces, size_t workspace_bytes,
+                                    int32_t streaming, void *stream)
+{
+    LaunchCtx ctx(stream);
+    if (int st = check_shape(n, block)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS || M < 1 || M > EQUARX_CALIB_MAX_CHAINS) return EQUARX_BAD_SHAPE;
+    if (!partials_bf16 || !out_bf16 || !workspaces) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    const size_t need = equarx_workspace_bytes(P, n, block);
+    if (workspace_bytes < need) return EQUARX_WORKSPACE_TOO_SMALL;
+    const int64_t nb = blocks_of(n, block);
+    const size_t codes = round_up((size_t)n, kWorkspaceAlign);
+    const size_t scales = round_up((size_t)nb * sizeof(float), kWorkspaceAlign);
+    for (int32_t m = 0; m < M; ++m) {
+        if (!out_bf16[m] || !workspaces[m]) return EQUARX_NULL_POINTER;
+        if (misaligned(out_bf16[m], kAlign) || misaligned(workspaces[m], kWorkspaceAlign)) return EQUARX_MISALIGNED;
+        Aliasing mem;       // chain m's inputs against everything any chain writes
+        for (int32_t i = 0; i < P; ++i) {
+            const void *x = partials_bf16[(size_t)m * P + i];
+            if (!x) return EQUARX_NULL_POINTER;
+            if (misaligned(x, kAlign)) return EQUARX_MISALIGNED;
+            mem.reads(x, (size_t)n * 2);
+        }
+        for (int32_t k = 0; k < M; ++k) {
+            mem.writes(out_bf16[k], (size_t)n * 2);
+            mem.writes(workspaces[k], need);
+        }
+        if (int st = mem.verdict()) return st;
+    }
+    const bool stream_wire = streaming != 0;
+    // pass by pass over all chains: chain m's wire i is read M-1 launches after it was written
+    for (int32_t pass = 0; pass <= P; ++pass) {
+        for (int32_t m = 0; m < M; ++m) {
+            char *w = static_cast<char *>(workspaces[m]);
+            int8_t *c[2] = {reinterpret_cast<int8_t *>(w), reinterpret_cast<int8_t *>(w + codes + scales)};
+            float *s[2] = {reinterpret_cast<float *>(w + codes), reinterpret_cast<float *>(w + 2 * codes + scales)};
+            const void *x = partials_bf16[(size_t)m * P + (pass < P ? pass : 0)];
+            if (pass == 0) {
+                do_quantize(x, n, block, c[0], s[0], ctx, stream_wire);
+            } else if (pass < P) {
+                do_hop(c[(pass - 1) & 1], s[(pass - 1) & 1], x, n, block, c[pass & 1], s[pass & 1], ctx, stream_wire);
+            } else {
+                do_dequantize(c[(P - 1) & 1], s[(P - 1) & 1], n, block, out_bf16[m], ctx, stream_wire);
+            }
+        }
+    }
     return ctx.status();
 }
 

@@ -17,8 +17,7 @@ from . import binding as eq
 from . import build
 from . import workloads as wl
 
-FIG7 = wl.Workload("fig7", P=8, rows=4096, hidden=4096, block=64, dist="normal", seed=1007,
-                   note="the tensor of the paper's speedup-vs-error experiment")
+FIG7 = wl.FIG7
 
 
 def _time_us(fn, sets, reps: int) -> float:

@@ -57,6 +57,11 @@ WORKLOADS = {
                          note="64 MiB per partial, heavy tails; block swept over 32/128/512"),
 }
 
+# The tensor of the paper's own accuracy/speed comparison of its flavours (Sec. 4.1, Fig. 7): (4096, 4096), N(0,1),
+# 8 devices, block size 64.  Not one of the benchmark's configs; used by the report tool and the parity tests.
+FIG7 = Workload("fig7", P=8, rows=4096, hidden=4096, block=64, dist="normal", seed=1007,
+                note="the (4096, 4096) N(0,1) tensor of Sec. 4.1 / Fig. 7: 8 devices, block 64")
+
 OUTLIER_FRACTION = 0.001   # share of hidden channels scaled up in the outlier recipe
 OUTLIER_GAIN = 50.0
 

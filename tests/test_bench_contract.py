@@ -34,10 +34,30 @@ def test_algorithmic_bytes():
     assert b.HBM_PEAK_GBPS == 8000.0
 
 
-def test_traffic_file_is_read():
+def test_traffic_file_is_read_only_for_the_library_it_was_made_with():
+    """The committed counter summary names the library build it measured; bench.py quotes it for that build only
+    (after a change to the kernels the figure is withheld until the profile is made again)."""
     b = _bench()
-    t = b.read_traffic()
+    with open(b.TRAFFIC_FILE) as f:
+        digests = [line.split()[1] for line in f if line.split()[:1] == ["library_digest"]]
+    assert len(digests) == 1 and len(digests[0]) == 64, "the profile must name the build it measured"
+    t = b.read_traffic(digests[0])
     assert t is not None and 0.98 * 88_768_512 < t < 1.1 * 88_768_512
+    assert b.read_traffic("0" * 64) is None
+
+
+def test_cold_wire_arrangement():
+    """Enough interleaved chains that the other chains' wire writes alone, between a wire's write and its read,
+    exceed the 256 MB cache."""
+    b = _bench()
+    n3 = 4096 * 5376
+    assert b.wire_bytes(n3, 256) == 22_020_096 + 344_064
+    for n, B in ((n3, 256), (2048 * 3840, 256), (33_554_432, 32), (33_554_432, 512)):
+        m = b.cold_chains(n, B)
+        assert 2 <= m <= 64 and (m - 1) * b.wire_bytes(n, B) >= 1.25 * (256 << 20) > (m - 2) * b.wire_bytes(n, B)
+    assert b.cold_chains(n3, 256) == 17
+    assert b.cold_chains(64 * 5376, 128) == 0 and b.cold_chains(4096, 256) == 0      # small messages: never cold
+    assert b.ends_bytes(8, n3, 256) == 664_731_648
 
 
 def test_more_than_one_gpu_is_refused():

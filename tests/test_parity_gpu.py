@@ -3,6 +3,8 @@
 Bar: int8 codes and fp32 scales bit-exact at every hop; the bf16 output bit-exact as well (the stated tolerance
 of one bf16 ulp, 2^-7 relative, is therefore met with room to spare and is asserted separately).
 """
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -342,6 +344,42 @@ def test_time_launch_span_brackets_the_hops(gpu, oracle):
     assert (gpu.host_u16(out) == want).all()
 
 
+@pytest.mark.parametrize("streaming", (False, True))
+def test_interleaved_chains_are_the_chain(gpu, oracle, streaming):
+    """The benchmark's cold-wire arrangement (several independent chains, launches interleaved pass by pass), with
+    cacheable and with non-temporal wire accesses, gives every chain the oracle's result."""
+    M, P, n, B = 3, 5, 2048 * 7 + 300, 128
+    sets_u16 = [[gpu.bf16_of(_values("lognormal", n, 8800 + 17 * m + p)) for p in range(P)] for m in range(M)]
+    sets = [[gpu.dev_bf16(p) for p in ps] for ps in sets_u16]
+    outs = [torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda") for _ in range(M)]
+    works = [eq.alloc_workspace(P, n, B) for _ in range(M)]
+    eq.equarx_calib_interleaved_chains(sets, B, outs, works, streaming)
+    torch.cuda.synchronize()
+    for m in range(M):
+        assert (gpu.host_u16(outs[m]) == oracle.reduce_chain(sets_u16[m], B)).all(), m
+
+
+def test_per_step_calls_compose_the_chain(gpu, oracle):
+    """The per-step entry points (non-temporal wire accesses) composed by hand give the chain entry point's bits,
+    wire for wire, including a hop in place."""
+    P, n, B = 6, 2048 * 3 * 5 + 2048 + 77, 64
+    parts_u16 = [gpu.bf16_of(_values("student", n, 9100 + p)) for p in range(P)]
+    want, wc, ws = oracle.reduce_chain(parts_u16, B, keep_wire=True)
+    parts = [gpu.dev_bf16(p) for p in parts_u16]
+    nb = eq.num_blocks(n, B)
+    c = torch.full((n,), 99, dtype=torch.int8, device="cuda")
+    s = torch.full((nb,), -7.0, dtype=torch.float32, device="cuda")
+    eq.equarx_quantize(parts[0], B, c, s)
+    for i in range(1, P):
+        eq.equarx_reduce_stage(c, s, parts[i], B, c, s)         # in place: the wire buffer is reused every step
+        torch.cuda.synchronize()
+        assert (c.cpu().numpy() == wc[i]).all() and (s.cpu().numpy().view(np.uint32) == ws[i].view(np.uint32)).all(), i
+    out = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_dequantize(c, s, B, out)
+    torch.cuda.synchronize()
+    assert (gpu.host_u16(out) == want).all()
+
+
 def test_timing_hooks_die_with_a_rejected_call(gpu, oracle):
     """Hooks armed before a call that fails validation are dropped by that call: the next, valid call neither
     records nor attaches them (the events keep the times of their own earlier records)."""
@@ -490,6 +528,54 @@ def test_full_size_large_message_sampled(gpu, oracle, B):
     _sampled_blocks_check(gpu, oracle, wl.WORKLOADS["c5_large"].with_block(B), n_sample=2000, seed=B)
 
 
+def test_full_size_fig7_tensor_sampled(gpu, oracle):
+    """The paper's own setting (Sec. 4.1 / Fig. 7: (4096, 4096), N(0,1), 8 devices, block 64) at full size: the
+    chain with every hop's wire on sampled blocks, and every flavour the figure compares -- both forms of each,
+    single launch and hop by hop -- on the same sampled blocks."""
+    w = wl.FIG7
+    assert (w.P, w.n, w.block) == (8, 4096 * 4096, 64)
+    _sampled_blocks_check(gpu, oracle, w, n_sample=3000, seed=64)
+    u16 = [wl.as_u16(p) for p in wl.make_partials(w)]
+    dev = [gpu.dev_bf16(p) for p in u16]
+    n, B, P = w.n, w.block, w.P
+    nb = n // B
+    blocks = np.unique(np.concatenate([[0, 1, nb - 2, nb - 1], _rng(65).integers(0, nb, 3000)]))
+    idx = (blocks[:, None] * B + np.arange(B)[None, :]).reshape(-1)
+    sub = [p[idx] for p in u16]
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    for name in ("rs_only", "ag_only", "semi", "semi_rs_only"):
+        flags = VARIANT_FLAGS[name]
+        want = _oracle_variant(oracle, sub, B, flags)
+        out.fill_(3.0)
+        eq.equarx_reduce_variant(dev, B, flags, out)
+        torch.cuda.synchronize()
+        assert (gpu.host_u16(out)[idx] == want).all(), name
+        if name != "ag_only":           # without a quantized reduce-scatter there is no hop-by-hop form
+            out.fill_(3.0)
+            eq.equarx_reduce_variant_hops(dev, B, flags, out, eq.alloc_variant_workspace(flags, P, n, B))
+            torch.cuda.synchronize()
+            assert (gpu.host_u16(out)[idx] == want).all(), name + " hop by hop"
+    # ring order: the sampled blocks of each shard against the pinned chain in that shard's own rotation
+    per = -(-nb // P)
+    for name in ("ring", "ring_rs_only"):
+        flags = VARIANT_FLAGS[name]
+        ag = not (flags & eq.AG_UNQUANTIZED)
+        for hops in (False, True):
+            out.fill_(3.0)
+            if hops:
+                eq.equarx_reduce_variant_hops(dev, B, flags, out, eq.alloc_variant_workspace(flags, P, n, B))
+            else:
+                eq.equarx_reduce_variant(dev, B, flags, out)
+            torch.cuda.synchronize()
+            got = gpu.host_u16(out)
+            for k in range(P):
+                mine = blocks[(blocks >= k * per) & (blocks < (k + 1) * per)]
+                ix = (mine[:, None] * B + np.arange(B)[None, :]).reshape(-1)
+                order = [(k + 1 + i) % P for i in range(P)]
+                want = oracle.reduce_stages([u16[d][ix] for d in order], B, True, ag)
+                assert (got[ix] == want).all(), (name, hops, k)
+
+
 # ----------------------------------------------------------------------------- the kernels' own arithmetic
 
 def test_block_quotients_equal_ieee_division_for_every_fp32(gpu):
@@ -607,11 +693,12 @@ def test_variant_workloads(gpu, oracle):
 
 @pytest.mark.parametrize("name", ("full", "rs_only", "semi", "semi_rs_only", "ring", "ring_rs_only"))
 @pytest.mark.parametrize("P", (1, 2, 3, 4, 5, 8, 9))
-def test_variant_hop_by_hop_parity(gpu, oracle, name, P):
+@pytest.mark.parametrize("B", (32, 64, 256, 512))
+def test_variant_hop_by_hop_parity(gpu, oracle, name, P, B):
     """The variants in the ring-imposed schedule (one launch per hop, wires in memory): the oracle's bits, which are
-    also the single-launch form's; output in place for odd P."""
+    also the single-launch form's; output in place for odd P; every lane-group width of the kernels."""
     flags = VARIANT_FLAGS[name]
-    n, B = 2048 * 7 + 5 * 64 + 24, 64
+    n = 2048 * 7 + 5 * B + 24
     parts = [gpu.bf16_of(_values("lognormal", n, 9300 + p)) for p in range(P)]
     want = _oracle_variant(oracle, parts, B, flags)
     dev = [gpu.dev_bf16(p) for p in parts]
@@ -1065,4 +1152,14 @@ def test_bench_prints_one_json_line_with_the_contract_keys(gpu):
     assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s"
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-3 and "traffic" in r
     c = d["cpu_baseline"]
-    assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
+    assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["sample"] and c["cpu_model"]
+    assert r["cold_wire"] is None           # a message this small is never cold: the figure is not reported
+    # a message large enough for the cold-wire arrangement: both fractions are on the line, each labelled
+    run = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--rows", "2048", "--steps", "8", "--warmup", "2",
+                          "--cpu-seconds", "0"], capture_output=True, text=True, timeout=170)
+    assert run.returncode == 0, run.stderr[-2000:]
+    d = json.loads(run.stdout.strip())
+    r = d["roofline"]
+    assert 0.2 < r["frac"] < 1.0 and 0.2 < r["cold_wire"]["frac"] < 1.0 and "warm" in r["measured"]
+    assert r["traffic_level"].startswith("bytes between L2") and d["chain"]["cold_wire"]["chains_interleaved"] >= 3
+    assert {"ms_per_step", "frac_of_hbm_peak", "cacheable_wire_ms_per_step"} <= set(d["chain"]["cold_wire"])
