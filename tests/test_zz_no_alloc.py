@@ -51,6 +51,38 @@ def test_static_workspace_matches_caller_workspace(oracle):
     assert (_u16(parts[3]) == want).all()
 
 
+@pytest.mark.gpu
+def test_static_workspace_under_graph_capture(oracle):
+    """What the entry point is for: captured in a HIP graph (after one eager call has looked the array's address up),
+    replayed several times on changing inputs with eager calls in between; every replay equals the eager result."""
+    assert torch.cuda.is_available()
+    P, n, B = 6, 2048 * 3 * 9 + 1000, 128
+    parts = [torch.zeros(n, dtype=torch.bfloat16, device="cuda") for _ in range(P)]
+    out = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    eager = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_quantized_static(parts, B, out)           # outside capture: resolves the static array's address
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        eq.equarx_reduce_quantized_static(parts, B, out)
+    for rep in range(4):
+        fresh = _partials(40 + rep, P, n)
+        for d, f in zip(parts, fresh):
+            d.copy_(f)
+        eq.equarx_reduce_quantized(parts, B, eager, eq.alloc_workspace(P, n, B))      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), rep
+        assert (_u16(out) == oracle.reduce_chain([_u16(p) for p in parts], B)).all(), rep
+        if rep == 1:        # an eager call of another size on the same array between two replays
+            small = _partials(77, 3, 4096)
+            o2 = torch.zeros(4096, dtype=torch.bfloat16, device="cuda")
+            eq.equarx_reduce_quantized_static(small, 256, o2)
+            torch.cuda.synchronize()
+            assert (_u16(o2) == oracle.reduce_chain([_u16(p) for p in small], 256)).all()
+
+
 def test_static_workspace_limit_is_enforced():
     """Sizes whose wire buffers do not fit the static array are rejected on the host, before any launch."""
     lib = eq.load()
