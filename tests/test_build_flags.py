@@ -37,7 +37,7 @@ def test_kernels_are_there_and_use_what_the_sources_say(device_asm):
     asm = device_asm["equarx_api.hip"]
     # the hop kernel of the benchmark's block size exists, widens int8 with byte-select converts, exchanges lanes
     # with DPP and the row swaps, and converts to bf16 in hardware where it writes bf16
-    assert re.search(r"^_ZN6equarx10hop_kernelILi256ELi\d+EEEv", asm, flags=re.M)
+    assert re.search(r"^_ZN6equarx10hop_kernelILi256ELi\d+ELb[01]EEEv", asm, flags=re.M)
     assert "v_permlane32_swap" in asm and "v_permlane16_swap" in asm and "row_mirror" in asm
     assert "v_cvt_pk_bf16_f32" in asm
     assert "v_perm_b32" in asm
