@@ -55,6 +55,12 @@ def ends_bytes(P: int, n: int, block: int) -> float:
     return fused_bytes(P, n) + 2.0 * max(P - 2, 0) * n * (1.0 + 4.0 / block)
 
 
+def input_sets(P: int, n: int) -> int:
+    """Resident copies of the inputs to rotate over: enough that together they are at least twice the Infinity
+    Cache, so that a set has left it when its turn comes again; between 2 and 64."""
+    return int(min(64, max(2, -(-2 * INFINITY_CACHE_BYTES // (2 * P * n)))))
+
+
 def wire_bytes(n: int, block: int) -> float:
     """Bytes of one wire buffer: int8 codes and fp32 scales."""
     return n * (1.0 + 4.0 / block)
@@ -186,9 +192,12 @@ def main() -> int:
     everything = args.only == "all"
 
     host = wl.make_partials(w)
-    # two resident input sets, used in turn, so that no step finds its inputs in the 256 MB Infinity Cache
+    # resident input sets, used in turn, so that no step finds its inputs in the 256 MB Infinity Cache: as many as it
+    # takes for the sets together to be twice that cache (two for the 27B shape, five for the 12B shape), at most 64
+    S = input_sets(P, n)
     sets = [[p.reshape(-1).cuda() for p in host]]
-    sets.append([p.clone() for p in sets[0]])
+    for _ in range(S - 1):
+        sets.append([p.clone() for p in sets[0]])
     out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
     work = eq.alloc_workspace(P, n, B)
     nb = eq.num_blocks(n, B)
@@ -253,9 +262,9 @@ def main() -> int:
             return statistics.fmean(a.elapsed_time(b) for a, b in pairs)
 
         calls = {
-            "hop": lambda k: eq.equarx_reduce_quantized(sets[k % 2], B, out, work),
-            "ends": lambda k: eq.equarx_reduce_quantized_fused_ends(sets[k % 2], B, out, work),
-            "fused": lambda k: eq.equarx_reduce_fused(sets[k % 2], B, out),
+            "hop": lambda k: eq.equarx_reduce_quantized(sets[k % S], B, out, work),
+            "ends": lambda k: eq.equarx_reduce_quantized_fused_ends(sets[k % S], B, out, work),
+            "fused": lambda k: eq.equarx_reduce_fused(sets[k % S], B, out),
         }
         descriptions = {
             "hop": "hop-by-hop, P+1 launches, wire written once and read once",
@@ -276,7 +285,7 @@ def main() -> int:
                 "effective_input_GBps": round(gbps(2.0 * P * n, ms), 1),
                 "algorithmic_bytes": own_bytes[name],
                 "frac_of_hbm_peak": frac(own_bytes[name], ms),
-                "inputs": "cold (two input sets in turn)",
+                "inputs": f"cold ({S} input sets in turn)",
                 "wire": "none" if name == "fused" else "warm (read by the launch after the one that wrote it)",
             }
         if "hop" in infos:
@@ -304,11 +313,11 @@ def main() -> int:
             qs = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(P - 1)]
 
             def flat_pipeline(k):
-                eq.equarx_quantize_batch(sets[k % 2][1:], B, qc, qs)
-                eq.equarx_reduce_flat(sets[k % 2][0], qc, qs, B, out)
+                eq.equarx_quantize_batch(sets[k % S][1:], B, qc, qs)
+                eq.equarx_reduce_flat(sets[k % S][0], qc, qs, B, out)
 
             flat_ms = timed_steps(flat_pipeline)
-            flat_kernel_ms = single_kernel_ms(lambda k: eq.equarx_reduce_flat(sets[k % 2][0], qc, qs, B, out), min(K, 50))
+            flat_kernel_ms = single_kernel_ms(lambda k: eq.equarx_reduce_flat(sets[k % S][0], qc, qs, B, out), min(K, 50))
             flat_kernel_bytes = n * (2.0 + (P - 1) * (1.0 + 4.0 / B) + 2.0)
             flat_pipe_bytes = flat_kernel_bytes + (P - 1) * n * (2.0 + 1.0 + 4.0 / B)
             ref = torch.zeros(n, dtype=torch.float64, device="cuda")
@@ -357,7 +366,7 @@ def main() -> int:
                 codes = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(2)]
                 scales = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(2)]
                 traffic_only_ms, _ = per_launch_ms(
-                    lambda k: eq.equarx_calib_hop_traffic(sets[k % 2], B, codes[0], scales[0], codes[1], scales[1]),
+                    lambda k: eq.equarx_calib_hop_traffic(sets[k % S], B, codes[0], scales[0], codes[1], scales[1]),
                     0, P - 1)
                 del codes, scales
         elif everything:
@@ -387,8 +396,7 @@ def main() -> int:
         cold = None
         M = cold_chains(n, B) if P > 1 and args.only in ("all", "cold") else 0
         if M:
-            more = [sets[0], sets[1]] + [[p.clone() for p in sets[0]] for _ in range(M - 2)]
-            more = more[:M]
+            more = (sets + [[p.clone() for p in sets[0]] for _ in range(max(M - S, 0))])[:M]
             outs = [torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(M)]
             works = [eq.alloc_workspace(P, n, B) for _ in range(M)]
             rounds = max(2, -(-K // M))

@@ -250,11 +250,9 @@ int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n
  * forms above keep it in registers).  Same bits as equarx_reduce_variant with
  * the same flags.
  *
- *   flags   any of EQUARX_AG_UNQUANTIZED, EQUARX_SEMI_LOOP, EQUARX_RING_ORDER,
- *           except the last two together.  EQUARX_RS_UNQUANTIZED is rejected
- *           (EQUARX_BAD_SHAPE): without a quantized reduce-scatter there is
- *           no wire to write; so is the per-shard semi-loop, built only as a
- *           single launch.
+ *   flags   any of EQUARX_AG_UNQUANTIZED, EQUARX_SEMI_LOOP, EQUARX_RING_ORDER.
+ *           EQUARX_RS_UNQUANTIZED is rejected (EQUARX_BAD_SHAPE): without a
+ *           quantized reduce-scatter there is no wire to write.
  *           full loop: Q_B(x_0), hops 1 .. P-2, and a last launch that performs
  *           hop P-1 and either the all-gather's quantize/dequantize pair or
  *           (EQUARX_AG_UNQUANTIZED) the narrowing to bf16: P launches.
@@ -264,9 +262,14 @@ int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n
  *           semi-loop (Sec. 3.3): the two half chains hop by hop, then one
  *           launch in which the owner (partials[0]) adds the two received wires
  *           to its own shard, counter-clockwise first: P launches.
+ *           semi-loop with EQUARX_RING_ORDER: P/2 launches, each of them one
+ *           iteration of the ring's semi-loop on all P shards -- both chains
+ *           of every shard advance one device per launch, as both directions
+ *           of a ring do -- then the owners' launch: P/2 + 1 launches.
  *   workspace  equarx_variant_workspace_bytes(flags, P, n, block) bytes, 256-byte
  *           aligned (the semi-loop keeps one chain's last wire while the other
- *           chain runs: three wire buffers instead of two).
+ *           chain runs: three wire buffers instead of two; in ring order each
+ *           direction ping-pongs between two of its own: four).
  * Other arguments as for equarx_reduce_quantized (out_bf16 may be a partial).
  */
 int equarx_reduce_variant_hops(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block,

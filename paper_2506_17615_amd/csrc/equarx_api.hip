@@ -248,11 +248,11 @@ inline int fill_table(const void *const *partials_bf16, int32_t P, int64_t n, Al
     return EQUARX_OK;
 }
 
-// The two (or three) ping-pong wire buffers inside a workspace: codes, then scales, each part rounded up to
+// The two (semi-loop: three, semi-loop in ring order: four) wire buffers inside a workspace: codes, then scales, each part rounded up to
 // the workspace alignment.
 struct WireBuffers {
-    int8_t *c[3];
-    float *s[3];
+    int8_t *c[4];
+    float *s[4];
 };
 
 inline WireBuffers carve_workspace(void *workspace, int64_t n, int64_t scales_count)
@@ -261,12 +261,55 @@ inline WireBuffers carve_workspace(void *workspace, int64_t n, int64_t scales_co
     const size_t scales = round_up((size_t)scales_count * sizeof(float), kWorkspaceAlign);
     char *w = static_cast<char *>(workspace);
     WireBuffers b;
-    for (int i = 0; i < 3; ++i) {       // the third pair exists only in the semi-loop's larger workspace
+    for (int i = 0; i < 4; ++i) {       // pairs beyond the second exist only in the semi-loop's larger workspaces
         b.c[i] = reinterpret_cast<int8_t *>(w + (size_t)i * (codes + scales));
         b.s[i] = reinterpret_cast<float *>(w + (size_t)i * (codes + scales) + codes);
     }
     return b;
 }
+
+// Semi-loop in ring order, hop by hop: h = P/2 launches in which both chains of every shard advance one device
+// (grid row = shard, grid layer = direction), then the owners' launch.  Wire buffers: direction d ping-pongs between
+// buffers 2d and 2d + 1.
+template <int B>
+void launch_semi_ring_hops(const PartialTable &tab, int P, int64_t n, bool ag, const WireBuffers &w, uint16_t *out,
+                           LaunchCtx &ctx)
+{
+    const int64_t nb = blocks_of(n, B);
+    const int64_t shard_elems = (nb + P - 1) / P * B;       // ceil(nb / P) blocks per shard, as the single launch
+    const unsigned gx = grid_for(shard_elems, kTilesHop), gy = (unsigned)P;
+    const int h = P / 2, count[2] = {P - 1 - h, h};
+    for (int t = 0; t < h; ++t) {
+        WirePair in, to;
+        for (int d = 0; d < 2; ++d) {
+            in.codes[d] = w.c[2 * d + ((t + 1) & 1)];
+            in.scales[d] = w.s[2 * d + ((t + 1) & 1)];
+            to.codes[d] = w.c[2 * d + (t & 1)];
+            to.scales[d] = w.s[2 * d + (t & 1)];
+        }
+        ctx.launch3d(semi_ring_step_kernel<B, kTilesHop>, gx, gy, 2u, kThreads, tab, P, t, n, shard_elems, in, to);
+    }
+    WireTable wires;
+    for (int r = 0; r < kMaxPartials; ++r) {
+        wires.codes[r] = nullptr;
+        wires.scales[r] = nullptr;
+    }
+    int received = 0;
+    for (int d = 0; d < 2; ++d) {       // counter-clockwise first, as the single launch adds them
+        if (count[d] == 0) continue;
+        wires.codes[received] = w.c[2 * d + ((count[d] - 1) & 1)];
+        wires.scales[received] = w.s[2 * d + ((count[d] - 1) & 1)];
+        ++received;
+    }
+    if (ag) {
+        ctx.launch2d(semi_ring_owner_kernel<B, kTilesFlat, true>, grid_for(shard_elems, kTilesFlat), gy, kThreads, tab, P, n, shard_elems,
+                     wires, received, out);
+    } else {
+        ctx.launch2d(semi_ring_owner_kernel<B, kTilesFlat, false>, grid_for(shard_elems, kTilesFlat), gy, kThreads, tab, P, n,
+                     shard_elems, wires, received, out);
+    }
+}
+
 
 // ---- strided (Sec. 3.2) geometry ----
 
@@ -351,7 +394,9 @@ const char *equarx_status_string(int status)
         case EQUARX_BAD_SHAPE: return "bad shape: n < 0, P out of range, or forbidden overlap of buffers";
         case EQUARX_BAD_BLOCK: return "block size must be 32, 64, 128, 256 or 512";
         case EQUARX_MISALIGNED: return "a data pointer is not 16-byte aligned";
-        case EQUARX_WORKSPACE_TOO_SMALL: return "workspace is smaller than equarx_workspace_bytes()";
+        case EQUARX_WORKSPACE_TOO_SMALL:
+            return "workspace (the caller's, or the static array of equarx_reduce_quantized_static) is smaller than the "
+                   "call needs: see equarx_workspace_bytes() / equarx_variant_workspace_bytes()";
         case EQUARX_DEVICE_ERROR: return "the HIP runtime reported an error at kernel launch";
         default: return "unknown status";
     }
@@ -635,7 +680,10 @@ int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n
 size_t equarx_variant_workspace_bytes(uint32_t flags, int32_t P, int64_t n, int32_t block)
 {
     const size_t two = equarx_workspace_bytes(P, n, block);
-    return (flags & EQUARX_SEMI_LOOP) ? two / 2 * 3 : two;      // the semi-loop keeps one chain's wire while the other runs
+    if (!(flags & EQUARX_SEMI_LOOP)) return two;
+    // the semi-loop keeps one chain's wire while the other runs (three buffers); in ring order both chains advance
+    // in the same launch and each ping-pongs between two buffers of its own (four)
+    return (flags & EQUARX_RING_ORDER) ? two * 2 : two / 2 * 3;
 }
 
 int equarx_reduce_variant_hops(const void *const *partials_bf16, int32_t P, int64_t n, int32_t block, uint32_t flags,
@@ -647,7 +695,6 @@ int equarx_reduce_variant_hops(const void *const *partials_bf16, int32_t P, int6
     if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_AG_UNQUANTIZED | EQUARX_RING_ORDER)) return EQUARX_BAD_SHAPE;
     const bool semi = flags & EQUARX_SEMI_LOOP, ag = !(flags & EQUARX_AG_UNQUANTIZED);
     const bool ring = flags & EQUARX_RING_ORDER;
-    if (semi && ring) return EQUARX_BAD_SHAPE;      // the per-shard semi-loop exists as a single launch only
     if (!partials_bf16) return EQUARX_NULL_POINTER;
     if (n == 0) return EQUARX_OK;
     if (!out_bf16 || !workspace) return EQUARX_NULL_POINTER;
@@ -666,6 +713,12 @@ int equarx_reduce_variant_hops(const void *const *partials_bf16, int32_t P, int6
     float *const s[3] = {w.s[0], w.s[1], w.s[2]};
     uint16_t *out = static_cast<uint16_t *>(out_bf16);
 
+    if (semi && ring) {     // every launch is one semi-loop iteration of the ring on all P shards, both directions
+#define CALL(BB) launch_semi_ring_hops<BB>(tab, P, n, ag, w, out, ctx)
+        EQUARX_DISPATCH_BLOCK(block, CALL)
+#undef CALL
+        return ctx.status();
+    }
     if (!semi) {
         if (P == 1) {       // no hop: one launch quantizes/dequantizes (or copies) partial 0
 #define CALL(BB) launch_chain<BB>(tab, P, n, true, ag, ring, out, nullptr, nullptr, 0, 0, ctx)

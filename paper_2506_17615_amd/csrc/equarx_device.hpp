@@ -1215,4 +1215,63 @@ __global__ __launch_bounds__(kThreads) void flat_kernel(const uint16_t *local, c
     }
 }
 
+// ---------------------------------------------------------------- semi-loop in ring order, hop by hop
+//
+// What all devices of a ring do in one iteration of the semi-loop reduce-scatter (Sec. 3.3), as one launch: grid
+// row k works on shard k, which device k owns; the devices k+1, k+2, ... sit around it at positions 1, 2, ....
+// With h = P/2 the counter-clockwise chain runs over positions h+1, h+2, ..., P-1 and the clockwise chain over
+// positions h, h-1, ..., 1; in iteration t both advance one device (blockIdx.z picks the direction), so the whole
+// reduce-scatter takes h iterations, as the paper's N/2.  Same bodies as the plain per-pass kernels.
+
+struct WirePair {           // one wire buffer per direction
+    int8_t *codes[2];
+    float *scales[2];
+};
+
+template <int B, int K>
+__global__ __launch_bounds__(kThreads) void semi_ring_step_kernel(const PartialTable tab, int P, int t, int64_t n,
+                                                                  int64_t shard_elems, const WirePair in,
+                                                                  const WirePair out)
+{
+    const Span sp = workgroup_span<K>(n, shard_elems, 0);       // rot = the owner's device number
+    if (!sp.any) return;
+    const int dir = blockIdx.z, h = P / 2;
+    const int count = dir == 0 ? P - 1 - h : h;                 // devices in this direction's chain
+    if (t >= count) return;                                     // the shorter chain has already arrived
+    int dev = sp.rot + (dir == 0 ? h + 1 + t : h - t);          // < 2P
+    if (dev >= P) dev -= P;
+    const uint16_t *x = tab.x[dev];
+    const int64_t nb = (sp.hi + B - 1) / B;
+    const bool full = sp.wg_at + kTileElems * K <= sp.hi;
+    if (t == 0) {
+        if (full) {
+            quantize_body<B, K, true>(x, sp.hi, out.codes[dir], out.scales[dir], nb, sp.wg_at);
+        } else {
+            quantize_body<B, K, false>(x, sp.hi, out.codes[dir], out.scales[dir], nb, sp.wg_at);
+        }
+    } else if (full) {
+        hop_body<B, K, true>(in.codes[dir], in.scales[dir], x, sp.hi, out.codes[dir], out.scales[dir], nb, sp.wg_at);
+    } else {
+        hop_body<B, K, false>(in.codes[dir], in.scales[dir], x, sp.hi, out.codes[dir], out.scales[dir], nb, sp.wg_at);
+    }
+}
+
+// The owner's last step: its own shard plus the wires that arrived (counter-clockwise first), then the all-gather's
+// quantize/dequantize pair or the plain narrowing.
+template <int B, int K, bool kAG>
+__global__ __launch_bounds__(kThreads) void semi_ring_owner_kernel(const PartialTable tab, int P, int64_t n,
+                                                                   int64_t shard_elems, const WireTable wires,
+                                                                   int received, uint16_t *out)
+{
+    const Span sp = workgroup_span<K>(n, shard_elems, 0);
+    if (!sp.any) return;
+    const uint16_t *own = tab.x[sp.rot >= P ? sp.rot - P : sp.rot];
+    const int64_t nb = (sp.hi + B - 1) / B;
+    if (sp.wg_at + kTileElems * K <= sp.hi) {
+        flat_body<B, K, true, false, kAG, true>(own, wires, received, sp.hi, out, nullptr, nullptr, nb, sp.wg_at);
+    } else {
+        flat_body<B, K, true, false, kAG, false>(own, wires, received, sp.hi, out, nullptr, nullptr, nb, sp.wg_at);
+    }
+}
+
 }  // namespace equarx

@@ -130,6 +130,13 @@ public:
     template <typename... KArgs, typename... Args>
     void launch2d(void (*kernel)(KArgs...), unsigned grid_x, unsigned grid_y, unsigned threads, Args... args)
     {
+        launch3d(kernel, grid_x, grid_y, 1u, threads, args...);
+    }
+
+    template <typename... KArgs, typename... Args>
+    void launch3d(void (*kernel)(KArgs...), unsigned grid_x, unsigned grid_y, unsigned grid_z, unsigned threads,
+                  Args... args)
+    {
         static_assert(sizeof...(KArgs) == sizeof...(Args), "kernel argument count");
         if (error_ != hipSuccess) return;
         const int index = launches_++;
@@ -143,9 +150,9 @@ public:
         hipEvent_t e1 = index == 0 ? hooks_.launch_stop : nullptr;
         const void *fn = reinterpret_cast<const void *>(kernel);
         if (e0 || e1) {
-            note(hipExtLaunchKernel(fn, dim3(grid_x, grid_y), dim3(threads), slots, 0, stream_, e0, e1, 0));
+            note(hipExtLaunchKernel(fn, dim3(grid_x, grid_y, grid_z), dim3(threads), slots, 0, stream_, e0, e1, 0));
         } else {
-            note(hipLaunchKernel(fn, dim3(grid_x, grid_y), dim3(threads), slots, 0, stream_));
+            note(hipLaunchKernel(fn, dim3(grid_x, grid_y, grid_z), dim3(threads), slots, 0, stream_));
         }
         if (error_ == hipSuccess && hooks_.span_stop && index == hooks_.span_last) {
             note(hipEventRecord(hooks_.span_stop, stream_));

@@ -53,6 +53,7 @@ def main() -> int:
     out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
     work = eq.alloc_workspace(P, n, B)
     work3 = eq.alloc_variant_workspace(eq.SEMI_LOOP, P, n, B)
+    work4 = eq.alloc_variant_workspace(eq.SEMI_LOOP | eq.RING_ORDER, P, n, B)
     nb = eq.num_blocks(n, B)
     qc = [torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(P - 1)]
     qs = [torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(P - 1)]
@@ -84,6 +85,9 @@ def main() -> int:
         ("full-loop RS+AG, ring order per shard", lambda ps: eq.equarx_reduce_variant(ps, B, eq.RING_ORDER, out)),
         ("full-loop RS+AG, ring order, hop by hop (P launches)",
          lambda ps: eq.equarx_reduce_variant_hops(ps, B, eq.RING_ORDER, out, work3)),
+        ("semi-loop RS+AG, ring order per shard", lambda ps: eq.equarx_reduce_variant(ps, B, eq.SEMI_LOOP | eq.RING_ORDER, out)),
+        ("semi-loop RS+AG, ring order, hop by hop (P/2+1 launches)",
+         lambda ps: eq.equarx_reduce_variant_hops(ps, B, eq.SEMI_LOOP | eq.RING_ORDER, out, work4)),
         ("all-to-all: batched quantize + flat reduce", flat),
     ]
     if B in eq.STRIDED_CHUNKS and n % (1024 * B) == 0:

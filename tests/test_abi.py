@@ -156,8 +156,10 @@ def test_validation_rejects_before_launch(lib):
     vh, vw = lib.equarx_reduce_variant_hops, lib.equarx_variant_workspace_bytes
     assert vw(0, 4, n, blk) == need and vw(B.SEMI_LOOP, 4, n, blk) == need // 2 * 3 and vw(0, 4, n, 100) == 0
     need3 = vw(B.SEMI_LOOP, 4, n, blk)
-    for bad_flags in (B.RS_UNQUANTIZED, B.RING_ORDER | B.RS_UNQUANTIZED, 16, B.SEMI_LOOP | B.RING_ORDER):
+    for bad_flags in (B.RS_UNQUANTIZED, B.RING_ORDER | B.RS_UNQUANTIZED, 16, B.SEMI_LOOP | B.RS_UNQUANTIZED):
         assert vh(ok4, 4, n, blk, bad_flags, OUT, WS, need3, None) == B.STATUS_BAD_SHAPE
+    assert vw(B.SEMI_LOOP | B.RING_ORDER, 4, n, blk) == 2 * need       # both chains advance per launch: four wire buffers
+    assert vh(ok4, 4, n, blk, B.SEMI_LOOP | B.RING_ORDER, OUT, WS, need3, None) == B.STATUS_WORKSPACE_TOO_SMALL
     assert vh(ok4, 0, n, blk, 0, OUT, WS, need3, None) == B.STATUS_BAD_SHAPE
     assert vh(None, 4, n, blk, 0, OUT, WS, need3, None) == B.STATUS_NULL_POINTER
     assert vh(ok4, 4, n, blk, 0, OUT, None, need3, None) == B.STATUS_NULL_POINTER

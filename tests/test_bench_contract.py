@@ -58,6 +58,9 @@ def test_cold_wire_arrangement():
     assert b.cold_chains(n3, 256) == 17
     assert b.cold_chains(64 * 5376, 128) == 0 and b.cold_chains(4096, 256) == 0      # small messages: never cold
     assert b.ends_bytes(8, n3, 256) == 664_731_648
+    # input sets rotated over: together at least twice the cache (27B shape 2, 12B shape 5, 64 MiB messages 2, small ones capped)
+    assert b.input_sets(8, n3) == 2 and b.input_sets(8, 2048 * 3840) == 5 and b.input_sets(8, 33_554_432) == 2
+    assert b.input_sets(16, 64 * 5376) == 49 and b.input_sets(4, 4096) == 64
 
 
 def test_more_than_one_gpu_is_refused():

@@ -557,9 +557,10 @@ def test_full_size_fig7_tensor_sampled(gpu, oracle):
             assert (gpu.host_u16(out)[idx] == want).all(), name + " hop by hop"
     # ring order: the sampled blocks of each shard against the pinned chain in that shard's own rotation
     per = -(-nb // P)
-    for name in ("ring", "ring_rs_only"):
+    for name in ("ring", "ring_rs_only", "ring_semi", "ring_semi_rs_only"):
         flags = VARIANT_FLAGS[name]
         ag = not (flags & eq.AG_UNQUANTIZED)
+        semi = bool(flags & eq.SEMI_LOOP)
         for hops in (False, True):
             out.fill_(3.0)
             if hops:
@@ -571,8 +572,10 @@ def test_full_size_fig7_tensor_sampled(gpu, oracle):
             for k in range(P):
                 mine = blocks[(blocks >= k * per) & (blocks < (k + 1) * per)]
                 ix = (mine[:, None] * B + np.arange(B)[None, :]).reshape(-1)
-                order = [(k + 1 + i) % P for i in range(P)]
-                want = oracle.reduce_stages([u16[d][ix] for d in order], B, True, ag)
+                if semi:            # device k owns the shard, the devices k+1, k+2, ... sit around it
+                    want = oracle.reduce_semi_loop([u16[(k + i) % P][ix] for i in range(P)], B, ag)
+                else:               # the chain starts at device k+1 and ends on device k
+                    want = oracle.reduce_stages([u16[(k + 1 + i) % P][ix] for i in range(P)], B, True, ag)
                 assert (got[ix] == want).all(), (name, hops, k)
 
 
@@ -691,7 +694,8 @@ def test_variant_workloads(gpu, oracle):
             assert (gpu.gpu_variant(parts, w.block, flags) == _oracle_variant(oracle, parts, w.block, flags)).all(), (case, name)
 
 
-@pytest.mark.parametrize("name", ("full", "rs_only", "semi", "semi_rs_only", "ring", "ring_rs_only"))
+@pytest.mark.parametrize("name", ("full", "rs_only", "semi", "semi_rs_only", "ring", "ring_rs_only", "ring_semi",
+                                  "ring_semi_rs_only"))
 @pytest.mark.parametrize("P", (1, 2, 3, 4, 5, 8, 9))
 @pytest.mark.parametrize("B", (32, 64, 256, 512))
 def test_variant_hop_by_hop_parity(gpu, oracle, name, P, B):
@@ -714,7 +718,7 @@ def test_variant_hop_by_hop_workload_shape(gpu, oracle):
     parts = [wl.as_u16(p) for p in wl.make_partials(w)]
     oracle.set_threads(8)
     try:
-        for name in ("rs_only", "semi", "semi_rs_only", "ring", "ring_rs_only"):
+        for name in ("rs_only", "semi", "semi_rs_only", "ring", "ring_rs_only", "ring_semi", "ring_semi_rs_only"):
             flags = VARIANT_FLAGS[name]
             dev = [gpu.dev_bf16(p) for p in parts]
             out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
