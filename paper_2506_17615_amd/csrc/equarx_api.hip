@@ -413,7 +413,7 @@ int equarx_quantize(const void *x_bf16, int64_t n, int32_t block, int8_t *codes,
     mem.reads(x_bf16, (size_t)n * 2);
     mem.writes(codes, (size_t)n);
     mem.writes(scales, (size_t)blocks_of(n, block) * sizeof(float));
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     do_quantize(x_bf16, n, block, codes, scales, ctx, kWireLeavesTheDevice);
     return ctx.status();
 }
@@ -445,7 +445,7 @@ int equarx_quantize_batch(const void *const *x_bf16, int8_t *const *codes, float
         tab.codes[i] = codes[i];
         tab.scales[i] = scales[i];
     }
-    if (int st = mem.verdict()) return st;      // two tensors sharing an output, or an output inside an input
+    if (int st = mem.check()) return st;      // two tensors sharing an output, or an output inside an input
 #define CALL(BB)                                                                                                  \
     ctx.launch2d(quantize_batch_kernel<BB, kTilesQuantize>, grid_for(n, kTilesQuantize), (unsigned)count, kThreads, \
                  tab, n, blocks_of(n, BB))
@@ -466,7 +466,7 @@ int equarx_dequantize(const int8_t *codes, const float *scales, int64_t n, int32
     mem.reads(codes, (size_t)n);
     mem.reads(scales, (size_t)blocks_of(n, block) * sizeof(float));
     mem.writes(out_bf16, (size_t)n * 2);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     do_dequantize(codes, scales, n, block, out_bf16, ctx, kWireLeavesTheDevice);
     return ctx.status();
 }
@@ -482,7 +482,7 @@ static int check_hop_memory(const int8_t *codes_in, const float *scales_in, cons
     mem.reads(local_bf16, (size_t)n * 2);
     mem.writes(codes_out, (size_t)n, 1);
     mem.writes(scales_out, (size_t)scales_count * sizeof(float), 2);
-    return mem.verdict();
+    return mem.check();
 }
 
 int equarx_reduce_stage(const int8_t *codes_in, const float *scales_in, const void *local_bf16, int64_t n,
@@ -533,7 +533,7 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
         mem.writes(workspace, need);
         w = carve_workspace(workspace, n, nb);
     }
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
 
     int8_t *c_prev = keep_wire ? wire_codes : w.c[0];
     float *s_prev = keep_wire ? wire_scales : w.s[0];
@@ -563,7 +563,7 @@ int equarx_reduce_quantized_static(const void *const *partials_bf16, int32_t P, 
     Aliasing mem;
     if (int st = check_partials(partials_bf16, P, n, mem)) return st;
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     unsigned char *wire = nullptr;
     if (int st = static_scratch(&wire)) return st;
     // Nothing in the array has to start at zero: pass 0 writes wire buffer 0 completely before hop 1 reads it,
@@ -593,7 +593,7 @@ int equarx_reduce_quantized_fused_ends(const void *const *partials_bf16, int32_t
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
     uint16_t *out = static_cast<uint16_t *>(out_bf16);
     if (P <= 2) {       // both ends meet: the chain is one launch and needs no wire
-        if (int st = mem.verdict()) return st;
+        if (int st = mem.check()) return st;
 #define CALL(BB) launch_chain<BB>(tab, P, n, true, true, false, out, nullptr, nullptr, 0, 0, ctx)
         EQUARX_DISPATCH_BLOCK(block, CALL)
 #undef CALL
@@ -604,7 +604,7 @@ int equarx_reduce_quantized_fused_ends(const void *const *partials_bf16, int32_t
     const size_t need = equarx_workspace_bytes(P, n, block);
     if (workspace_bytes < need) return EQUARX_WORKSPACE_TOO_SMALL;
     mem.writes(workspace, need);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     const WireBuffers w = carve_workspace(workspace, n, blocks_of(n, block));
     int8_t *const c[2] = {w.c[0], w.c[1]};
     float *const s[2] = {w.s[0], w.s[1]};
@@ -634,7 +634,7 @@ int equarx_reduce_fused(const void *const *partials_bf16, int32_t P, int64_t n, 
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
     mem.writes(wire_codes, (size_t)P * c_step);
     mem.writes(wire_scales, (size_t)P * s_step * sizeof(float));
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
 #define CALL(BB)                                                                                               \
     launch_chain<BB>(tab, P, n, true, true, false, static_cast<uint16_t *>(out_bf16), wire_codes, wire_scales, \
                      c_step, s_step, ctx)
@@ -663,7 +663,7 @@ int equarx_reduce_variant(const void *const *partials_bf16, int32_t P, int64_t n
     Aliasing mem;
     if (int st = fill_table(partials_bf16, P, n, mem, tab)) return st;
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     uint16_t *out = static_cast<uint16_t *>(out_bf16);
     if (semi) {
 #define CALL(BB) launch_semi<BB>(tab, P, n, ag, ring, out, ctx)
@@ -706,7 +706,7 @@ int equarx_reduce_variant_hops(const void *const *partials_bf16, int32_t P, int6
     if (int st = fill_table(partials_bf16, P, n, mem, tab)) return st;
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
     mem.writes(workspace, need);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
 
     const WireBuffers w = carve_workspace(workspace, n, blocks_of(n, block));
     int8_t *const c[3] = {w.c[0], w.c[1], w.c[2]};
@@ -808,7 +808,7 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
         tab.codes[r] = codes[r];
         tab.scales[r] = scales[r];
     }
-    if (int st = mem.verdict()) return st;          // outputs must not share memory with inputs or one another
+    if (int st = mem.check()) return st;          // outputs must not share memory with inputs or one another
 #define CALL(BB)                                                                                                  \
     launch_flat<BB>(static_cast<const uint16_t *>(local_bf16), tab, R, n, static_cast<uint16_t *>(out_bf16), codes_out, \
                     scales_out, ctx)
@@ -828,7 +828,7 @@ int equarx_quantize_strided(const void *x_bf16, int64_t n, int32_t chunks, int8_
     mem.reads(x_bf16, (size_t)n * 2);
     mem.writes(codes, (size_t)n);
     mem.writes(scales, (size_t)(n / chunks) * sizeof(float));
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     do_quantize_strided(x_bf16, n, chunks, codes, scales, ctx);
     return ctx.status();
 }
@@ -845,7 +845,7 @@ int equarx_dequantize_strided(const int8_t *codes, const float *scales, int64_t 
     mem.reads(codes, (size_t)n);
     mem.reads(scales, (size_t)(n / chunks) * sizeof(float));
     mem.writes(out_bf16, (size_t)n * 2);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     do_dequantize_strided(codes, scales, n, chunks, out_bf16, ctx);
     return ctx.status();
 }
@@ -882,7 +882,7 @@ int equarx_reduce_quantized_strided(const void *const *partials_bf16, int32_t P,
     if (workspace_bytes < need) return EQUARX_WORKSPACE_TOO_SMALL;
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
     mem.writes(workspace, need);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     const WireBuffers w = carve_workspace(workspace, n, n / chunks);
     do_quantize_strided(partials_bf16[0], n, chunks, w.c[0], w.s[0], ctx);
     for (int32_t i = 1; i < P; ++i) {
@@ -906,7 +906,7 @@ int equarx_reduce_fused_strided(const void *const *partials_bf16, int32_t P, int
     Aliasing mem;
     if (int st = fill_table(partials_bf16, P, n, mem, tab)) return st;
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
 #define CALL(RR) \
     ctx.launch(chain_strided_kernel<RR>, strided_grid(n, chunks), kThreads, tab, P, static_cast<uint16_t *>(out_bf16))
     EQUARX_DISPATCH_CHUNKS(chunks, CALL)

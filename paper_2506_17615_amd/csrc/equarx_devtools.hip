@@ -24,7 +24,7 @@ int equarx_calib_copy(const void *src, void *dst, size_t bytes, void *stream)
     Aliasing mem;
     mem.reads(src, bytes);
     mem.writes(dst, bytes);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     const int64_t nvec = (int64_t)(bytes / 16);
     const int64_t per_wg = kThreads * 4;
     ctx.launch(copy_kernel, (unsigned)((nvec + per_wg - 1) / per_wg), kThreads, static_cast<const u32x4 *>(src),
@@ -64,7 +64,7 @@ int equarx_calib_hop_traffic(const void *const *partials_bf16, int32_t P, int64_
     mem.writes(scales0, scale_bytes);
     mem.writes(codes1, (size_t)n);
     mem.writes(scales1, scale_bytes);
-    if (int st = mem.verdict()) return st;
+    if (int st = mem.check()) return st;
     const int64_t lanes = n / kLaneElems;
     u32x2 *c[2] = {reinterpret_cast<u32x2 *>(codes0), reinterpret_cast<u32x2 *>(codes1)};
     float *s[2] = {scales0, scales1};
@@ -112,7 +112,7 @@ int equarx_calib_interleaved_chains(const void *const *partials_bf16, int32_t M,
             mem.writes(out_bf16[k], (size_t)n * 2);
             mem.writes(workspaces[k], need);
         }
-        if (int st = mem.verdict()) return st;
+        if (int st = mem.check()) return st;
     }
     const bool stream_wire = streaming != 0;
     // pass by pass over all chains: chain m's wire i is read M-1 launches after it was written

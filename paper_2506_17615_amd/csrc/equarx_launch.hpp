@@ -56,7 +56,7 @@ public:
     void writes(const void *p, size_t bytes, int tag = 0) { add(p, bytes, tag, true); }
 
     // EQUARX_OK, or EQUARX_BAD_SHAPE if a written range overlaps another range where it may not.
-    int verdict() const
+    int check() const
     {
         if (overflow_) return EQUARX_BAD_SHAPE;
         for (int i = 0; i < count_; ++i) {
