@@ -99,6 +99,32 @@ def gpu_chain_fused_ends(partials_u16, B):
     return host_u16(out)
 
 
+def gpu_chain_per_step(partials_u16, B):
+    """The chain composed by hand from the per-step entry points (quantize, P-1 hops, dequantize: the calls a device
+    of a ring makes, with their non-temporal wire accesses); returns out (u16), wire codes [P,n], scales [P,nb]."""
+    parts = [dev_bf16(p) for p in partials_u16]
+    P, n = len(parts), parts[0].numel()
+    nb = eq.num_blocks(n, B)
+    rows_c = [torch.full((n,), 99, dtype=torch.int8, device="cuda") for _ in range(P)]       # one allocation per wire:
+    rows_s = [torch.full((nb,), -7.0, dtype=torch.float32, device="cuda") for _ in range(P)]  # each is aligned
+    eq.equarx_quantize(parts[0], B, rows_c[0], rows_s[0])
+    for i in range(1, P):
+        eq.equarx_reduce_stage(rows_c[i - 1], rows_s[i - 1], parts[i], B, rows_c[i], rows_s[i])
+    out = torch.full((n,), 7.0, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_dequantize(rows_c[P - 1], rows_s[P - 1], B, out)
+    torch.cuda.synchronize()
+    return host_u16(out), torch.stack(rows_c).cpu().numpy(), torch.stack(rows_s).cpu().numpy()
+
+
+def gpu_chain_static(partials_u16, B):
+    """Runs equarx_reduce_quantized_static (wire buffers in the library's static device array)."""
+    parts = [dev_bf16(p) for p in partials_u16]
+    out = torch.full((parts[0].numel(),), 7.0, dtype=torch.bfloat16, device="cuda")
+    eq.equarx_reduce_quantized_static(parts, B, out)
+    torch.cuda.synchronize()
+    return host_u16(out)
+
+
 def gpu_variant(partials_u16, B, flags):
     parts = [dev_bf16(p) for p in partials_u16]
     out = torch.full((parts[0].numel(),), 7.0, dtype=torch.bfloat16, device="cuda")

@@ -178,6 +178,11 @@ def _check_chain(gpu, oracle, parts, B):
     assert (gpu.gpu_chain_fused(parts, B, keep_wire=False) == oo).all()
     # hop by hop with both ends fused (P-1 launches)
     assert (gpu.gpu_chain_fused_ends(parts, B) == oo).all()
+    # the per-step entry points composed by hand (non-temporal wire accesses): same wire at every hop, same output
+    sout, swc, sws = gpu.gpu_chain_per_step(parts, B)
+    assert (sout == oo).all() and (swc == owc).all() and (sws.view(np.uint32) == ows.view(np.uint32)).all()
+    # the chain whose wire buffers live in the library's static array
+    assert (gpu.gpu_chain_static(parts, B) == oo).all()
 
 
 CHAIN_CASES = {
