@@ -28,8 +28,9 @@
  *     buffer of the call, not even partly -- EQUARX_BAD_SHAPE -- except where
  *     an entry point says that an output may BE an input; the two must then
  *     coincide exactly.  Buffers that are only read may overlap freely.
- *   - The library keeps no state between calls and may be called from several
- *     threads at once (on different streams, or on one).
+ *   - The library keeps no state between calls (the one exception, the static
+ *     array of equarx_reduce_quantized_static, is described there) and may be
+ *     called from several threads at once (on different streams, or on one).
  *   - Pointers must be 16-byte aligned (8-byte for codes, 4 for scales is not
  *     enough: every data pointer is checked against 16).
  *   - Supported block sizes: 32, 64, 128, 256, 512.
@@ -59,7 +60,7 @@ typedef enum equarx_status {
     EQUARX_BAD_SHAPE = 2,           /* n < 0, P < 1, P > EQUARX_MAX_PARTIALS, or overlap that is not allowed */
     EQUARX_BAD_BLOCK = 3,           /* block not in {32, 64, 128, 256, 512} */
     EQUARX_MISALIGNED = 4,          /* a data pointer is not 16-byte aligned */
-    EQUARX_WORKSPACE_TOO_SMALL = 5, /* workspace_bytes < equarx_workspace_bytes(...) */
+    EQUARX_WORKSPACE_TOO_SMALL = 5, /* workspace_bytes (or the static array) < what the call needs */
     EQUARX_DEVICE_ERROR = 6         /* a kernel launch of this call returned a HIP error */
 } equarx_status;
 
@@ -162,8 +163,8 @@ int equarx_reduce_quantized(const void *const *partials_bf16, int32_t P, int64_t
  * allocates and frees nothing, on the device or through any library.
  *
  *   - equarx_workspace_bytes(P, n, block) above EQUARX_STATIC_WORKSPACE_BYTES
- *     is EQUARX_WORKSPACE_TOO_SMALL (80 MiB covers 64 Mi elements at block 32
- *     and every configuration of the benchmark list).
+ *     is EQUARX_WORKSPACE_TOO_SMALL (80 MiB covers a 64 MiB bf16 message,
+ *     32 Mi elements, at block 32: 72 MiB; larger blocks need less).
  *   - The first call on a GPU looks the array's address up
  *     (hipGetSymbolAddress; EQUARX_DEVICE_ERROR if that fails); make it
  *     outside a graph capture.

@@ -92,6 +92,9 @@ def test_static_workspace_limit_is_enforced():
     assert eq.workspace_bytes(2, n_fit, 32) <= eq.STATIC_WORKSPACE_BYTES
     n_big = n_fit + (1 << 20)
     assert eq.workspace_bytes(2, n_big, 32) > eq.STATIC_WORKSPACE_BYTES
+    # every configuration of the benchmark list fits, the 64 MiB message at block 32 included
+    for n, B in ((4096, 256), (2048 * 3840, 256), (4096 * 5376, 256), (64 * 5376, 128), (33_554_432, 32), (33_554_432, 512)):
+        assert 0 < eq.workspace_bytes(8, n, B) <= eq.STATIC_WORKSPACE_BYTES
     assert lib.equarx_reduce_quantized_static(table, 2, n_big, 32, A + (1 << 33), None) == eq.STATUS_WORKSPACE_TOO_SMALL
     assert lib.equarx_reduce_quantized_static(table, 2, 1 << 30, 512, A + (1 << 33), None) == eq.STATUS_WORKSPACE_TOO_SMALL
     assert lib.equarx_reduce_quantized_static(table, 2, 4096, 256, None, None) == eq.STATUS_NULL_POINTER
