@@ -383,6 +383,15 @@ def main() -> int:
                 b.record(stream)
             torch.cuda.synchronize()
             empty_us = statistics.median(a.elapsed_time(b) for a, b in ev) * 1e3 / 256
+        if empty_us:        # what the launches alone cost each schedule, and the time no such schedule can beat
+            launches = {"hop": P + 1, "ends": max(P - 1, 1), "fused": 1}
+            for name, info in infos.items():
+                floor_us = launches[name] * empty_us
+                bound_us = floor_us + own_bytes[name] / (HBM_PEAK_GBPS * 1e9) * 1e6
+                info["launches"] = launches[name]
+                info["launch_floor_us"] = round(floor_us, 2)
+                info["floor_plus_bytes_at_hbm_peak_us"] = round(bound_us, 2)
+                info["frac_of_that_bound"] = round(bound_us / (info["ms_per_step"] * 1e3), 4)
         if everything:      # calibration: what a plain 16-byte copy reaches on this device over the same footprint
             src = torch.empty(2 * P * n // 2, dtype=torch.uint8, device="cuda")
             dst = torch.empty_like(src)
