@@ -359,3 +359,15 @@ def reduce_chain_strided(partials, chunks: int, keep_wire: bool = False, lib=Non
         wc = np.stack([from_block_major(row, chunks) for row in wc])
         return from_block_major(out, chunks), wc, ws
     return from_block_major(reduce_chain(moved, chunks, lib=lib), chunks)
+
+
+def reduce_stages_strided(partials, chunks: int, quantize_rs: bool = True, quantize_ag: bool = True, lib=None) -> np.ndarray:
+    """The full-loop chain with the stage knob (Sec. 3.4) in the strided block geometry (Sec. 3.2)."""
+    moved = [to_block_major(_arr(p, np.uint16), chunks) for p in partials]
+    return from_block_major(reduce_stages(moved, chunks, quantize_rs, quantize_ag, lib=lib), chunks)
+
+
+def reduce_semi_loop_strided(partials, chunks: int, quantize_ag: bool = True, lib=None) -> np.ndarray:
+    """The semi-loop chain (Sec. 3.3; partials[0] owns the result) in the strided block geometry (Sec. 3.2)."""
+    moved = [to_block_major(_arr(p, np.uint16), chunks) for p in partials]
+    return from_block_major(reduce_semi_loop(moved, chunks, quantize_ag, lib=lib), chunks)

@@ -687,3 +687,50 @@ def pin_ring_variants(lib=None):
 
 
 ALL_PINS += [pin_ring_variants]
+
+
+def pin_strided_variants(lib=None):
+    """The flavours of Sec. 3.3 / 3.4 in the paper's own block geometry (Sec. 3.2): the elements at one position of
+    every chunk of a minishard form one block, so gathering them with a plain stride and running the pinned
+    contiguous flavour on that single block must give the strided result at exactly those elements -- for every
+    knob setting and the semi-loop, at positions in different minishards.  And the paper's Fig. 7 error figures
+    hold in its own geometry too (i.i.d. values: the statistics do not depend on which elements share a scale)."""
+    chunks, P = 32, 5
+    n = 2 * o.CHUNK * chunks
+    parts = _chain_inputs(131, P, n, heavy=True)
+    got = {
+        (True, True): o.reduce_stages_strided(parts, chunks, True, True, lib=lib),
+        (True, False): o.reduce_stages_strided(parts, chunks, True, False, lib=lib),
+        (False, True): o.reduce_stages_strided(parts, chunks, False, True, lib=lib),
+        (False, False): o.reduce_stages_strided(parts, chunks, False, False, lib=lib),
+    }
+    semi = {ag: o.reduce_semi_loop_strided(parts, chunks, ag, lib=lib) for ag in (True, False)}
+    assert (got[(True, True)] == o.reduce_chain_strided(parts, chunks)).all()
+    assert len({g.tobytes() for g in got.values()} | {g.tobytes() for g in semi.values()}) == 6      # all different
+    for m, j in ((0, 0), (0, 517), (0, 1023), (1, 1), (1, 640)):
+        idx = m * o.CHUNK * chunks + np.arange(chunks) * o.CHUNK + j
+        block = [p[idx] for p in parts]
+        for (rs, ag), g in got.items():
+            assert (g[idx] == o.reduce_stages(block, chunks, rs, ag)).all(), (m, j, rs, ag)
+        for ag, g in semi.items():
+            assert (g[idx] == o.reduce_semi_loop(block, chunks, ag)).all(), (m, j, ag)
+    # Fig. 7 in the paper's own geometry: 8 devices, block 64 = 64 chunks, N(0,1)
+    gold = read_golden("fig7_error.txt")
+    P8, B = int(gold["devices"]), int(gold["block"])
+    n8 = 4 * o.CHUNK * B
+    parts8 = _chain_inputs(2025, P8, n8)
+    ref = np.zeros(n8, np.float64)
+    for p in parts8:
+        ref += bf16_bits_to_f32(p).astype(np.float64)
+    base = bf16_bits_to_f32(_bf16(ref.astype(np.float32))).astype(np.float64)
+    mse = lambda out: float(np.mean((bf16_bits_to_f32(out).astype(np.float64) - base) ** 2))
+    full = mse(o.reduce_stages_strided(parts8, B, True, True, lib=lib))
+    semi8 = mse(o.reduce_semi_loop_strided(parts8, B, True, lib=lib))
+    ag_only = mse(o.reduce_stages_strided(parts8, B, False, True, lib=lib))
+    assert gold["full_loop_rs_ag"] / 1.5 <= full <= gold["full_loop_rs_ag"] * 1.5, full
+    assert gold["semi_loop_rs_ag"] / 1.5 <= semi8 <= gold["semi_loop_rs_ag"] * 1.5, semi8
+    assert gold["full_loop_ag_only"] / 1.5 <= ag_only <= gold["full_loop_ag_only"] * 1.5, ag_only
+    assert ag_only < semi8 < full
+
+
+ALL_PINS += [pin_strided_variants]

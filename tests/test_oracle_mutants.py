@@ -111,9 +111,22 @@ PY_MUTANTS = {
     "ring_ignores_semi_flag": ("        if semi:\n            order", "        if False:\n            order"),
     "ring_starts_at_own_device": ("return [(shard + 1 + i) % P for i in range(P)]", "return [(shard + i) % P for i in range(P)]"),
     "ring_walks_backwards": ("return [(shard + 1 + i) % P for i in range(P)]", "return [(shard - 1 - i) % P for i in range(P)]"),
+    "strided_stages_drops_rs_knob": ("from_block_major(reduce_stages(moved, chunks, quantize_rs, quantize_ag, lib=lib), chunks)",
+                                     "from_block_major(reduce_stages(moved, chunks, True, quantize_ag, lib=lib), chunks)"),
+    "strided_stages_swaps_knobs": ("from_block_major(reduce_stages(moved, chunks, quantize_rs, quantize_ag, lib=lib), chunks)",
+                                   "from_block_major(reduce_stages(moved, chunks, quantize_ag, quantize_rs, lib=lib), chunks)"),
+    "strided_stages_not_moved_back": ("from_block_major(reduce_stages(moved, chunks, quantize_rs, quantize_ag, lib=lib), chunks)",
+                                      "reduce_stages(moved, chunks, quantize_rs, quantize_ag, lib=lib)"),
+    "strided_semi_is_the_full_loop": ("from_block_major(reduce_semi_loop(moved, chunks, quantize_ag, lib=lib), chunks)",
+                                      "from_block_major(reduce_stages(moved, chunks, True, quantize_ag, lib=lib), chunks)"),
+    "strided_semi_contiguous_blocks": ("from_block_major(reduce_semi_loop(moved, chunks, quantize_ag, lib=lib), chunks)",
+                                       "reduce_semi_loop([_arr(p, np.uint16) for p in partials], chunks, quantize_ag, lib=lib)"),
     "shards_not_on_block_boundaries": ("per = (nb + P - 1) // P\n    return [(min(n, k * per * B), min(n, (k + 1) * per * B)) for k in range(P)]",
                                        "per = (n + P - 1) // P\n    return [(min(n, k * per), min(n, (k + 1) * per)) for k in range(P)]"),
 }
+
+
+FRONT_END = ("reduce_ring", "ring_order", "shard_bounds", "reduce_stages_strided", "reduce_semi_loop_strided")
 
 
 def _mutated_front_end(tmp_path, old, new):
@@ -134,7 +147,7 @@ def _mutated_front_end(tmp_path, old, new):
 @pytest.mark.parametrize("name", sorted(PY_MUTANTS))
 def test_pins_catch_front_end_mutant(oracle, tmp_path, monkeypatch, name):
     mod = _mutated_front_end(tmp_path, *PY_MUTANTS[name])
-    for attr in ("reduce_ring", "ring_order", "shard_bounds"):
+    for attr in FRONT_END:
         monkeypatch.setattr(o, attr, getattr(mod, attr))
     failed = _failing_pins(None, first_only=True)
     assert failed, f"no pin noticed the planted mistake {name!r}"
@@ -142,6 +155,6 @@ def test_pins_catch_front_end_mutant(oracle, tmp_path, monkeypatch, name):
 
 def test_unmutated_front_end_copy_passes(oracle, tmp_path, monkeypatch):
     mod = _mutated_front_end(tmp_path, "import ctypes\n", "import ctypes  \n")
-    for attr in ("reduce_ring", "ring_order", "shard_bounds"):
+    for attr in FRONT_END:
         monkeypatch.setattr(o, attr, getattr(mod, attr))
-    assert [p for p in ("pin_ring_order", "pin_ring_variants") if p in _failing_pins(None)] == []
+    assert [p for p in ("pin_ring_order", "pin_ring_variants", "pin_strided_variants") if p in _failing_pins(None)] == []
