@@ -75,6 +75,14 @@ def cold_chains(n: int, block: int) -> int:
     return m if m <= 64 else 0
 
 
+def cold_flat_pipelines(P: int, n: int, block: int) -> int:
+    """Independent all-to-all pipelines to interleave (all batched quantizes, then all flat reduces) so that the
+    P-1 wires of one are cold when its reduce reads them: the other pipelines' wire writes in between exceed the
+    Infinity Cache by a quarter.  0 if that takes more than 16 pipelines."""
+    m = int(-(-1.25 * INFINITY_CACHE_BYTES // ((P - 1) * wire_bytes(n, block)))) + 1
+    return m if m <= 16 else 0
+
+
 def read_traffic(library_digest: str):
     """Bytes per hop launch between L2 and the memory fabric, from the committed rocprofv3 counter summary, if that
     summary was made with the library as it is built now; else None.  A profile, not a live measurement."""
@@ -317,6 +325,28 @@ def main() -> int:
                 eq.equarx_reduce_flat(sets[k % S][0], qc, qs, B, out)
 
             flat_ms = timed_steps(flat_pipeline)
+            # the same pipelines with every wire cold when it is read: M of them side by side, wires of their own
+            flat_cold_ms, Mf = None, cold_flat_pipelines(P, n, B)
+            if Mf:
+                fc = [[torch.empty(n, dtype=torch.int8, device="cuda") for _ in range(P - 1)] for _ in range(Mf)]
+                fs = [[torch.empty(nb, dtype=torch.float32, device="cuda") for _ in range(P - 1)] for _ in range(Mf)]
+
+                def flat_round(k):
+                    for m in range(Mf):
+                        eq.equarx_quantize_batch(sets[(k * Mf + m) % S][1:], B, fc[m], fs[m])
+                    for m in range(Mf):
+                        eq.equarx_reduce_flat(sets[(k * Mf + m) % S][0], fc[m], fs[m], B, out)
+
+                for k in range(2):
+                    flat_round(k)
+                torch.cuda.synchronize()
+                rounds = max(2, K // Mf)
+                t0 = time.perf_counter()
+                for k in range(rounds):
+                    flat_round(k)
+                torch.cuda.synchronize()
+                flat_cold_ms = (time.perf_counter() - t0) * 1e3 / (rounds * Mf)
+                del fc, fs
             flat_kernel_ms = single_kernel_ms(lambda k: eq.equarx_reduce_flat(sets[k % S][0], qc, qs, B, out), min(K, 50))
             flat_kernel_bytes = n * (2.0 + (P - 1) * (1.0 + 4.0 / B) + 2.0)
             flat_pipe_bytes = flat_kernel_bytes + (P - 1) * n * (2.0 + 1.0 + 4.0 / B)
@@ -332,6 +362,13 @@ def main() -> int:
                 "effective_input_GBps": round(gbps(2.0 * P * n, flat_ms), 1),
                 "algorithmic_bytes": flat_pipe_bytes,
                 "frac_of_hbm_peak": frac(flat_pipe_bytes, flat_ms),
+                "cold_wire": None if flat_cold_ms is None else {
+                    "arrangement": f"{Mf} independent pipelines side by side: all batched quantizes, then all flat "
+                                   "reduces; between a wire's write and its read the others write more than the "
+                                   "Infinity Cache holds",
+                    "ms_per_step": round(flat_cold_ms, 5),
+                    "frac_of_hbm_peak": frac(flat_pipe_bytes, flat_cold_ms)},
+                "wire_access": "non-temporal (the wires cross devices in an all-to-all)",
                 "flat_kernel_avg_launch_us": round(flat_kernel_ms * 1e3, 3),
                 "flat_kernel_frac_of_hbm_peak": frac(flat_kernel_bytes, flat_kernel_ms),
                 "rel_l2_vs_exact_sum": flat_rel,

@@ -35,9 +35,10 @@
  *     enough: every data pointer is checked against 16).
  *   - Supported block sizes: 32, 64, 128, 256, 512.
  *   - equarx_quantize, equarx_reduce_stage and equarx_dequantize are the calls
- *     one device of a ring makes per step: the wire they read arrived from
- *     another device and the wire they write leaves for one, so they access
- *     it with non-temporal hints (read once; not read here again).  The chain
+ *     one device of a ring makes per step, equarx_quantize_batch and
+ *     equarx_reduce_flat the calls around an all-to-all: the wire they read
+ *     arrived from another device and the wire they write leaves for one, so
+ *     they access it with non-temporal hints (read once; not read here again).  The chain
  *     entry points run every step on this device and keep the wire cacheable
  *     for the next launch.  Same results either way; a chain composed by hand
  *     from the per-step calls on one device is a few percent slower than
@@ -324,6 +325,13 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
  *   equarx_reduce_stage_strided: codes_out / scales_out may BE codes_in / scales_in.
  *   equarx_reduce_fused_strided: the same chain in one launch (running sums in
  *            registers, no wire traffic, no workspace); same bits.
+ *   equarx_reduce_variant_strided: the flavours of Sec. 3.3 / 3.4 in this
+ *            geometry, one launch each: flags as for equarx_reduce_variant
+ *            (EQUARX_SEMI_LOOP with partials[0] as the owner,
+ *            EQUARX_RS_UNQUANTIZED, EQUARX_AG_UNQUANTIZED, same forbidden
+ *            combinations) except EQUARX_RING_ORDER, which this geometry does
+ *            not offer (EQUARX_BAD_SHAPE).  flags == 0 gives the bits of
+ *            equarx_reduce_fused_strided.  out_bf16 may BE one of the partials.
  */
 int equarx_quantize_strided(const void *x_bf16, int64_t n, int32_t chunks,
                             int8_t *codes, float *scales, void *stream);
@@ -336,6 +344,8 @@ int equarx_reduce_quantized_strided(const void *const *partials_bf16, int32_t P,
                                     void *out_bf16, void *workspace, size_t workspace_bytes, void *stream);
 int equarx_reduce_fused_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
                                 void *out_bf16, void *stream);
+int equarx_reduce_variant_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
+                                  uint32_t flags, void *out_bf16, void *stream);
 
 /* Bytes of workspace equarx_reduce_quantized needs (0 for invalid arguments). */
 size_t equarx_workspace_bytes(int32_t P, int64_t n, int32_t block);

@@ -49,6 +49,7 @@ SIGNATURES = {
     "equarx_reduce_stage_strided": (ctypes.c_int, [_vp, _vp, _vp, _i64, _i32, _vp, _vp, _vp]),
     "equarx_reduce_quantized_strided": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp]),
     "equarx_reduce_fused_strided": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp]),
+    "equarx_reduce_variant_strided": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp]),
     "equarx_workspace_bytes": (_sz, [_i32, _i64, _i32]),
     "equarx_num_blocks": (_i64, [_i64, _i32]),
     "equarx_wire_row_codes": (_i64, [_i64]),
@@ -385,6 +386,20 @@ def equarx_reduce_fused_strided(partials, chunks: int, out_bf16) -> None:
     table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
     _check(load().equarx_reduce_fused_strided(table, P, n, chunks, _ptr(out_bf16), _stream()),
            "equarx_reduce_fused_strided")
+
+
+def equarx_reduce_variant_strided(partials, chunks: int, flags: int, out_bf16) -> None:
+    """Semi-loop / stage-knob flavours of the chain in the strided geometry, one launch."""
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+        if p.numel() != n:
+            raise ValueError("partials differ in length")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    _check(load().equarx_reduce_variant_strided(table, P, n, chunks, flags, _ptr(out_bf16), _stream()),
+           "equarx_reduce_variant_strided")
 
 
 def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:

@@ -198,27 +198,40 @@ void launch_semi(const PartialTable &tab, int P, int64_t n, bool ag, bool ring, 
 #endif
 constexpr int kTilesFlat = EQUARX_TILES_FLAT;
 
-template <int B>
-void launch_flat(const uint16_t *local, const WireTable &tab, int R, int64_t n, uint16_t *out, int8_t *codes_out,
-                 float *scales_out, LaunchCtx &ctx, bool ag = true)
+template <int B, bool kStream>
+void launch_flat_as(const uint16_t *local, const WireTable &tab, int R, int64_t n, uint16_t *out, int8_t *codes_out,
+                    float *scales_out, LaunchCtx &ctx, bool ag)
 {
     const unsigned grid = grid_for(n, kTilesFlat);
     const int64_t nb = blocks_of(n, B);
     if (!ag) {      // bf16 output of the unquantized sum; callers pass out and no wire
-        ctx.launch(flat_kernel<B, kTilesFlat, true, false, false>, grid, kThreads, local, tab, R, n, out, codes_out, scales_out, nb);
+        ctx.launch(flat_kernel<B, kTilesFlat, true, false, false, kStream>, grid, kThreads, local, tab, R, n, out, codes_out, scales_out, nb);
     } else if (out && codes_out) {
-        ctx.launch(flat_kernel<B, kTilesFlat, true, true>, grid, kThreads, local, tab, R, n, out, codes_out, scales_out, nb);
+        ctx.launch(flat_kernel<B, kTilesFlat, true, true, true, kStream>, grid, kThreads, local, tab, R, n, out, codes_out, scales_out, nb);
     } else if (out) {
-        ctx.launch(flat_kernel<B, kTilesFlat, true, false>, grid, kThreads, local, tab, R, n, out, codes_out, scales_out, nb);
+        ctx.launch(flat_kernel<B, kTilesFlat, true, false, true, kStream>, grid, kThreads, local, tab, R, n, out, codes_out, scales_out, nb);
     } else {
-        ctx.launch(flat_kernel<B, kTilesFlat, false, true>, grid, kThreads, local, tab, R, n, out, codes_out, scales_out, nb);
+        ctx.launch(flat_kernel<B, kTilesFlat, false, true, true, kStream>, grid, kThreads, local, tab, R, n, out, codes_out, scales_out, nb);
     }
 }
 
-// The three per-step entry points (equarx_quantize, equarx_reduce_stage, equarx_dequantize) are what a device of a
-// ring calls once per step: the wire they read came from another device and the wire they write goes to one, so
-// they access it with non-temporal hints.  The chain entry points, which run every step on this device, know that
-// the next launch reads what this one wrote and keep the wire cacheable.
+// streaming: the received wires are read, and the outgoing wire is written, with non-temporal hints.
+template <int B>
+void launch_flat(const uint16_t *local, const WireTable &tab, int R, int64_t n, uint16_t *out, int8_t *codes_out,
+                 float *scales_out, LaunchCtx &ctx, bool ag = true, bool streaming = false)
+{
+    if (streaming) {
+        launch_flat_as<B, true>(local, tab, R, n, out, codes_out, scales_out, ctx, ag);
+    } else {
+        launch_flat_as<B, false>(local, tab, R, n, out, codes_out, scales_out, ctx, ag);
+    }
+}
+
+// The per-step entry points are what a device calls once per step of a collective: equarx_quantize,
+// equarx_reduce_stage and equarx_dequantize in a ring, equarx_quantize_batch and equarx_reduce_flat around an
+// all-to-all.  The wire they read came from another device and the wire they write goes to one, so they access it
+// with non-temporal hints.  The chain entry points, which run every step on this device, know that the next launch
+// reads what this one wrote and keep the wire cacheable.
 constexpr bool kWireLeavesTheDevice = true;
 
 // The output of a chain may BE one of the partials (in-place reduction: every
@@ -447,8 +460,8 @@ int equarx_quantize_batch(const void *const *x_bf16, int8_t *const *codes, float
     }
     if (int st = mem.check()) return st;      // two tensors sharing an output, or an output inside an input
 #define CALL(BB)                                                                                                  \
-    ctx.launch2d(quantize_batch_kernel<BB, kTilesQuantize>, grid_for(n, kTilesQuantize), (unsigned)count, kThreads, \
-                 tab, n, blocks_of(n, BB))
+    ctx.launch2d(quantize_batch_kernel<BB, kTilesQuantize, kWireLeavesTheDevice>, grid_for(n, kTilesQuantize), (unsigned)count, \
+                 kThreads, tab, n, blocks_of(n, BB))
     EQUARX_DISPATCH_BLOCK(block, CALL)
 #undef CALL
     return ctx.status();
@@ -811,7 +824,7 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
     if (int st = mem.check()) return st;          // outputs must not share memory with inputs or one another
 #define CALL(BB)                                                                                                  \
     launch_flat<BB>(static_cast<const uint16_t *>(local_bf16), tab, R, n, static_cast<uint16_t *>(out_bf16), codes_out, \
-                    scales_out, ctx)
+                    scales_out, ctx, true, kWireLeavesTheDevice)
     EQUARX_DISPATCH_BLOCK(block, CALL)
 #undef CALL
     return ctx.status();
@@ -909,6 +922,41 @@ int equarx_reduce_fused_strided(const void *const *partials_bf16, int32_t P, int
     if (int st = mem.check()) return st;
 #define CALL(RR) \
     ctx.launch(chain_strided_kernel<RR>, strided_grid(n, chunks), kThreads, tab, P, static_cast<uint16_t *>(out_bf16))
+    EQUARX_DISPATCH_CHUNKS(chunks, CALL)
+#undef CALL
+    return ctx.status();
+}
+
+int equarx_reduce_variant_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
+                                  uint32_t flags, void *out_bf16, void *stream)
+{
+    LaunchCtx ctx(stream);
+    if (int st = check_strided(n, chunks)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_RS_UNQUANTIZED | EQUARX_AG_UNQUANTIZED)) return EQUARX_BAD_SHAPE;
+    const bool semi = flags & EQUARX_SEMI_LOOP, rs = !(flags & EQUARX_RS_UNQUANTIZED);
+    const bool ag = !(flags & EQUARX_AG_UNQUANTIZED);
+    if (!rs && !ag) return EQUARX_BAD_SHAPE;        // nothing quantized
+    if (semi && !rs) return EQUARX_BAD_SHAPE;       // the semi-loop is a reduce-scatter schedule
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign)) return EQUARX_MISALIGNED;
+    PartialTable tab;
+    Aliasing mem;
+    if (int st = fill_table(partials_bf16, P, n, mem, tab)) return st;
+    mem.writes(out_bf16, (size_t)n * 2, kInPlace);
+    if (int st = mem.check()) return st;
+    uint16_t *out = static_cast<uint16_t *>(out_bf16);
+    const unsigned grid = strided_grid(n, chunks);
+#define CALL(RR)                                                                                               \
+    do {                                                                                                       \
+        if (semi && ag) ctx.launch(variant_strided_kernel<RR, true, true, true>, grid, kThreads, tab, P, out); \
+        else if (semi) ctx.launch(variant_strided_kernel<RR, true, true, false>, grid, kThreads, tab, P, out); \
+        else if (rs && ag) ctx.launch(variant_strided_kernel<RR, false, true, true>, grid, kThreads, tab, P, out); \
+        else if (rs) ctx.launch(variant_strided_kernel<RR, false, true, false>, grid, kThreads, tab, P, out);  \
+        else ctx.launch(variant_strided_kernel<RR, false, false, true>, grid, kThreads, tab, P, out);          \
+    } while (0)
     EQUARX_DISPATCH_CHUNKS(chunks, CALL)
 #undef CALL
     return ctx.status();

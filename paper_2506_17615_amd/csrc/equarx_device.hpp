@@ -436,7 +436,7 @@ struct QuantizeBatch {
     float *scales[kMaxBatch];
 };
 
-template <int B, int K>
+template <int B, int K, bool kStream = false>
 __global__ __launch_bounds__(kThreads) void quantize_batch_kernel(const QuantizeBatch tab, int64_t n, int64_t nb)
 {
     const uint16_t *x = tab.x[blockIdx.y];
@@ -444,9 +444,9 @@ __global__ __launch_bounds__(kThreads) void quantize_batch_kernel(const Quantize
     float *scales = tab.scales[blockIdx.y];
     const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
     if (wg_at + kTileElems * K <= n) {
-        quantize_body<B, K, true>(x, n, codes, scales, nb, wg_at);
+        quantize_body<B, K, true, kStream>(x, n, codes, scales, nb, wg_at);
     } else {
-        quantize_body<B, K, false>(x, n, codes, scales, nb, wg_at);
+        quantize_body<B, K, false, kStream>(x, n, codes, scales, nb, wg_at);
     }
 }
 
@@ -1145,7 +1145,7 @@ struct WireTable {
     const float *scales[kMaxPartials];
 };
 
-template <int B, int K, bool kOutBf16, bool kOutWire, bool kAG, bool kFull>
+template <int B, int K, bool kOutBf16, bool kOutWire, bool kAG, bool kFull, bool kStream = false>
 __device__ __forceinline__ void flat_body(const uint16_t *local, const WireTable &tab, int R, int64_t n,
                                           uint16_t *out, int8_t *__restrict__ codes_out,
                                           float *__restrict__ scales_out, int64_t nb, int64_t wg_at)
@@ -1166,7 +1166,7 @@ __device__ __forceinline__ void flat_body(const uint16_t *local, const WireTable
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const int64_t at = wg_at + k * kTileElems + lane_at;
-            cv[k] = load_i8x8(c, at, n, kFull);
+            cv[k] = load_i8x8<kStream>(c, at, n, kFull);
             const int64_t blk = at / B;
             sv[k] = (kFull || blk < nb) ? sc[blk] : 0.0f;
         }
@@ -1189,7 +1189,7 @@ __device__ __forceinline__ void flat_body(const uint16_t *local, const WireTable
         float q[8], s;
         quantize_lane_f<G, true>(acc[k], q, s);
         if (kOutWire) {
-            store_i8x8(codes_out, at, n, kFull, pack_codes(q));
+            store_i8x8<kStream>(codes_out, at, n, kFull, pack_codes(q));
             if ((threadIdx.x % G) == 0 && (kFull || at < n)) scales_out[at / B] = s;
         }
         if (kOutBf16) {
@@ -1201,7 +1201,7 @@ __device__ __forceinline__ void flat_body(const uint16_t *local, const WireTable
     }
 }
 
-template <int B, int K, bool kOutBf16, bool kOutWire, bool kAG = true>
+template <int B, int K, bool kOutBf16, bool kOutWire, bool kAG = true, bool kStream = false>
 __global__ __launch_bounds__(kThreads) void flat_kernel(const uint16_t *local, const WireTable tab, int R,
                                                         int64_t n, uint16_t *out,
                                                         int8_t *__restrict__ codes_out, float *__restrict__ scales_out,
@@ -1209,9 +1209,9 @@ __global__ __launch_bounds__(kThreads) void flat_kernel(const uint16_t *local, c
 {
     const int64_t wg_at = (int64_t)blockIdx.x * (kTileElems * K);
     if (wg_at + kTileElems * K <= n) {
-        flat_body<B, K, kOutBf16, kOutWire, kAG, true>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
+        flat_body<B, K, kOutBf16, kOutWire, kAG, true, kStream>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
     } else {
-        flat_body<B, K, kOutBf16, kOutWire, kAG, false>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
+        flat_body<B, K, kOutBf16, kOutWire, kAG, false, kStream>(local, tab, R, n, out, codes_out, scales_out, nb, wg_at);
     }
 }
 

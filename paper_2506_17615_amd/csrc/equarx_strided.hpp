@@ -264,6 +264,146 @@ __global__ __launch_bounds__(kThreads) void chain_strided_kernel(const PartialTa
     }
 }
 
+// ---------------------------------------------------------------- flavours of the chain in the strided geometry
+//
+// The semi-loop reduce-scatter (Sec. 3.3) and the stage knob (Sec. 3.4), one
+// launch each, with the blocks of Sec. 3.2.  The running sums live in
+// registers as in chain_strided_kernel; a quantized send is one trip through
+// LDS for the scales of the lane's 8 positions.
+
+template <int R>
+__device__ __forceinline__ void load_strided(const uint16_t *x, const StridedSpot &sp, u32x4 (&xv)[R])
+{
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        xv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(x + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+    }
+}
+
+// scale and inverse scale of the lane's 8 blocks for the sums t.  Every thread of the workgroup calls this.
+template <int R>
+__device__ __forceinline__ void strided_quotients(const float (&t)[R][8], uint32_t (*red)[kSlicePos], float (&scale)[8],
+                                                  float (&inv)[8])
+{
+    uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < R; ++r) note_absmax(t[r], m);
+    across_chunks_max(m, red);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) block_quotients(__uint_as_float(m[j]), scale[j], inv[j]);
+}
+
+// One quantized send: acc <- fma(code(t), scale, acc).  kPositiveZero: the code of a value that rounds to zero is
+// +0.0 as the integer code's conversion is (needed only where the sign of a zero sum can reach the output, i.e.
+// when the all-gather is not quantized).
+template <int R, bool kPositiveZero>
+__device__ __forceinline__ void strided_send(const float (&t)[R][8], float (&acc)[R][8], uint32_t (*red)[kSlicePos])
+{
+    float scale[8], inv[8];
+    strided_quotients<R>(t, red, scale, inv);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float q = __builtin_rintf(t[r][j] * inv[j]);
+            if (kPositiveZero) q += 0.0f;
+            acc[r][j] = __builtin_fmaf(q, scale[j], acc[r][j]);
+        }
+    }
+}
+
+template <int R>
+__device__ __forceinline__ void widen_strided(const u32x4 (&xv)[R], float (&t)[R][8])
+{
+#pragma unroll
+    for (int r = 0; r < R; ++r) widen_bf16x8(xv[r], t[r]);
+}
+
+// t <- fma(code(t), scale, x): what the device holding x has after it received the quantized t.
+template <int R, bool kPositiveZero>
+__device__ __forceinline__ void strided_hop(float (&t)[R][8], const u32x4 (&xv)[R], uint32_t (*red)[kSlicePos])
+{
+    float next[R][8];
+    widen_strided<R>(xv, next);
+    strided_send<R, kPositiveZero>(t, next, red);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[r][j] = next[r][j];
+    }
+}
+
+// kSemi: the semi-loop with partials[0] as the owner (always a quantized reduce-scatter); otherwise the full loop in
+// array order with the reduce-scatter quantized (kRS) or added in plain fp32.  kAG: the finished sum is quantized
+// once more and dequantized; otherwise narrowed to bf16 directly.
+template <int R, bool kSemi, bool kRS, bool kAG>
+__global__ __launch_bounds__(kThreads) void variant_strided_kernel(const PartialTable tab, int P, uint16_t *out)
+{
+    static_assert(kRS || !kSemi, "the semi-loop is a quantized reduce-scatter");
+    __shared__ uint32_t red[kChunkGroups][kSlicePos];
+    constexpr int chunks = R * kChunkGroups;
+    const StridedSpot sp = strided_spot(chunks);
+
+    float sum[R][8];
+    u32x4 xv[R];
+    load_strided<R>(tab.x[0], sp, xv);
+    widen_strided<R>(xv, sum);
+    if (kSemi) {
+        const int h = P / 2;
+        float t[R][8];
+        if (h + 1 <= P - 1) {                       // h+1 -> h+2 -> ... -> P-1 -> owner: the shorter chain arrives first
+            load_strided<R>(tab.x[h + 1], sp, xv);
+            widen_strided<R>(xv, t);
+            for (int i = h + 2; i <= P - 1; ++i) {
+                load_strided<R>(tab.x[i], sp, xv);
+                strided_hop<R, !kAG>(t, xv, red);
+            }
+            strided_send<R, !kAG>(t, sum, red);
+        }
+        if (h >= 1) {                               // h -> h-1 -> ... -> 1 -> owner
+            load_strided<R>(tab.x[h], sp, xv);
+            widen_strided<R>(xv, t);
+            for (int i = h - 1; i >= 1; --i) {
+                load_strided<R>(tab.x[i], sp, xv);
+                strided_hop<R, !kAG>(t, xv, red);
+            }
+            strided_send<R, !kAG>(t, sum, red);
+        }
+    } else {
+        for (int i = 1; i < P; ++i) {
+            load_strided<R>(tab.x[i], sp, xv);
+            if (kRS) {
+                strided_hop<R, !kAG>(sum, xv, red);
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float xf[8];
+                    widen_bf16x8(xv[r], xf);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) sum[r][j] = sum[r][j] + xf[j];
+                }
+            }
+        }
+    }
+
+    float scale[8], inv[8];
+    if (kAG) strided_quotients<R>(sum, red, scale, inv);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float d[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            d[j] = kAG ? (__builtin_rintf(sum[r][j] * inv[j]) + 0.0f) * scale[j] : sum[r][j];
+        }
+        u32x4 w;
+        w.x = narrow_bf16x2(d[0], d[1]);
+        w.y = narrow_bf16x2(d[2], d[3]);
+        w.z = narrow_bf16x2(d[4], d[5]);
+        w.w = narrow_bf16x2(d[6], d[7]);
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(out + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+    }
+}
+
 // Dequantize in the strided geometry: element e uses scale (e / (1024*chunks)) * 1024 + e % 1024, so the 8
 // elements of a lane use 8 consecutive scales.  n is a multiple of 1024, hence of the 2048-element tile.
 template <int K>

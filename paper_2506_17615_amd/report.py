@@ -95,6 +95,10 @@ def main() -> int:
                      lambda ps: eq.equarx_reduce_quantized_strided(ps, B, out, work)))
         rows.append(("full-loop RS+AG, strided 8x128-chunk blocks, one launch",
                      lambda ps: eq.equarx_reduce_fused_strided(ps, B, out)))
+        for label, flags in (("full-loop RS only", eq.AG_UNQUANTIZED), ("full-loop AG only", eq.RS_UNQUANTIZED),
+                             ("semi-loop RS+AG", eq.SEMI_LOOP), ("semi-loop RS only", eq.SEMI_LOOP | eq.AG_UNQUANTIZED)):
+            rows.append((label + ", strided 8x128-chunk blocks",
+                         lambda ps, flags=flags: eq.equarx_reduce_variant_strided(ps, B, flags, out)))
 
     print(f"workload {w.name}: P={P}, n={n} ({w.rows} x {w.hidden}), block {B}, {w.dist}; MI355X, one GPU")
     print(f"{'flavour':58s} {'us':>8s} {'eff. input GB/s':>16s} {'MSE vs bf16 sum':>16s} {'rel-L2 vs exact':>16s}")

@@ -198,6 +198,14 @@ def test_validation_rejects_before_launch(lib):
     assert fs_(table(A, A, ODD, A), 4, ns, 64, OUT, None) == B.STATUS_MISALIGNED
     assert fs_(table(A, A, OUT + 16, A), 4, ns, 64, OUT, None) == B.STATUS_BAD_SHAPE
     assert fs_(None, 4, 0, 64, None, None) == B.STATUS_NULL_POINTER and fs_(ok4, 4, 0, 64, None, None) == B.STATUS_OK
+    vs_ = lib.equarx_reduce_variant_strided
+    assert vs_(ok4, 4, ns, 64, 0, None, None) == B.STATUS_NULL_POINTER and vs_(ok4, 4, ns, 96, 0, OUT, None) == B.STATUS_BAD_BLOCK
+    assert vs_(ok4, 4, ns + 8, 64, 0, OUT, None) == B.STATUS_BAD_SHAPE and vs_(ok4, 65, ns, 64, 0, OUT, None) == B.STATUS_BAD_SHAPE
+    for bad_flags in (B.RING_ORDER, B.RS_UNQUANTIZED | B.AG_UNQUANTIZED, B.SEMI_LOOP | B.RS_UNQUANTIZED, 16):
+        assert vs_(ok4, 4, ns, 64, bad_flags, OUT, None) == B.STATUS_BAD_SHAPE
+    assert vs_(table(A, A, ODD, A), 4, ns, 64, B.SEMI_LOOP, OUT, None) == B.STATUS_MISALIGNED
+    assert vs_(table(A, A, OUT + 16, A), 4, ns, 64, B.SEMI_LOOP, OUT, None) == B.STATUS_BAD_SHAPE
+    assert vs_(None, 4, 0, 64, 0, None, None) == B.STATUS_NULL_POINTER and vs_(ok4, 4, 0, 64, B.SEMI_LOOP, None, None) == B.STATUS_OK
     qb = lib.equarx_quantize_batch
     xs, cs, ss = table(A, A + 0x1000), table(A + 0x2000, A + 0x3000), table(A + 0x4000, A + 0x5000)
     assert qb(xs, cs, ss, 65, n, blk, None) == B.STATUS_BAD_SHAPE

@@ -58,6 +58,9 @@ def test_cold_wire_arrangement():
     assert b.cold_chains(n3, 256) == 17
     assert b.cold_chains(64 * 5376, 128) == 0 and b.cold_chains(4096, 256) == 0      # small messages: never cold
     assert b.ends_bytes(8, n3, 256) == 664_731_648
+    # all-to-all form: the P-1 wires of one pipeline are written at once, so a few pipelines side by side suffice
+    assert b.cold_flat_pipelines(8, n3, 256) == 4 and b.cold_flat_pipelines(8, 2048 * 3840, 256) == 8
+    assert b.cold_flat_pipelines(16, 64 * 5376, 128) == 0
     # input sets rotated over: together at least twice the cache (27B shape 2, 12B shape 5, 64 MiB messages 2, small ones capped)
     assert b.input_sets(8, n3) == 2 and b.input_sets(8, 2048 * 3840) == 5 and b.input_sets(8, 33_554_432) == 2
     assert b.input_sets(16, 64 * 5376) == 49 and b.input_sets(4, 4096) == 64

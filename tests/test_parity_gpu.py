@@ -1097,6 +1097,96 @@ def test_strided_bad_arguments(gpu):
     assert e.value.status == eq.STATUS_WORKSPACE_TOO_SMALL
 
 
+STRIDED_VARIANTS = ("full", "rs_only", "ag_only", "semi", "semi_rs_only")
+
+
+def _oracle_variant_strided(oracle, parts, chunks, flags):
+    ag = not (flags & eq.AG_UNQUANTIZED)
+    if flags & eq.SEMI_LOOP:
+        return oracle.reduce_semi_loop_strided(parts, chunks, ag)
+    return oracle.reduce_stages_strided(parts, chunks, not (flags & eq.RS_UNQUANTIZED), ag)
+
+
+@pytest.mark.parametrize("name", STRIDED_VARIANTS)
+@pytest.mark.parametrize("chunks", (32, 64, 128))
+def test_strided_variant_parity(gpu, oracle, name, chunks):
+    """Semi-loop and stage knob in the strided geometry: the oracle's bits for every device count's chain lengths
+    (P = 1, 2, 3: a chain of the semi-loop is missing or a single send), for values whose zeros carry a sign
+    ("sparse": products with -0.0) and for the extreme ranges; output in place for some."""
+    flags = VARIANT_FLAGS[name]
+    ms = 1024 * chunks
+    cases = [(1, 1, "normal"), (2, 2, "sparse"), (3, 3, "lognormal"), (4, 2, "tiny"), (5, 2, "sparse"), (8, 3, "student"),
+             (9, 1, "huge"), (16, 1, "normal")]
+    for k, (P, count, kind) in enumerate(cases):
+        n = count * ms
+        parts = [gpu.bf16_of(_values(kind, n, 9800 + 11 * p + P)) for p in range(P)]
+        want = _oracle_variant_strided(oracle, parts, chunks, flags)
+        dev = [gpu.dev_bf16(p) for p in parts]
+        out = dev[P // 2] if k % 2 else torch.full((n,), 5.0, dtype=torch.bfloat16, device="cuda")
+        eq.equarx_reduce_variant_strided(dev, chunks, flags, out)
+        torch.cuda.synchronize()
+        got = gpu.host_u16(out)
+        assert (got == want).all(), (name, chunks, P, kind, int((got != want).sum()))
+        if name == "full":
+            assert (want == oracle.reduce_chain_strided(parts, chunks)).all()
+
+
+def test_strided_variant_full_size_sampled(gpu, oracle):
+    """The Fig. 7 tensor ((4096, 4096), N(0,1), 8 devices, block 64 = 64 chunks) in the paper's own geometry, every
+    flavour the figure compares: sampled minishards against the oracle, and the figure's error figures and their
+    order on the whole output."""
+    w = wl.FIG7
+    chunks = w.block
+    u16 = [wl.as_u16(p) for p in wl.make_partials(w)]
+    dev = [gpu.dev_bf16(p) for p in u16]
+    ms = 1024 * chunks
+    total = w.n // ms
+    pick = np.unique(np.concatenate([[0, total - 1], _rng(66).integers(0, total, 20)]))
+    idx = (pick[:, None] * ms + np.arange(ms)[None, :]).reshape(-1)
+    sub = [p[idx] for p in u16]
+    ref = torch.zeros(w.n, dtype=torch.float64, device="cuda")
+    for d in dev:
+        ref += d.double()
+    base = ref.float().to(torch.bfloat16).double()
+    out = torch.empty(w.n, dtype=torch.bfloat16, device="cuda")
+    mse = {}
+    oracle.set_threads(8)
+    try:
+        for name in STRIDED_VARIANTS:
+            flags = VARIANT_FLAGS[name]
+            out.fill_(3.0)
+            eq.equarx_reduce_variant_strided(dev, chunks, flags, out)
+            torch.cuda.synchronize()
+            assert (gpu.host_u16(out)[idx] == _oracle_variant_strided(oracle, sub, chunks, flags)).all(), name
+            mse[name] = float(((out.double() - base) ** 2).mean())
+    finally:
+        oracle.set_threads(1)
+    assert mse["ag_only"] < mse["semi"] < mse["full"] and mse["rs_only"] < mse["full"]
+    assert 0.0014 / 1.5 < mse["full"] < 0.0014 * 1.5 and 0.001 / 1.5 < mse["semi"] < 0.001 * 1.5
+    assert 0.0003 / 1.5 < mse["ag_only"] < 0.0003 * 1.5
+    fused = torch.empty_like(out)
+    eq.equarx_reduce_fused_strided(dev, chunks, fused)
+    eq.equarx_reduce_variant_strided(dev, chunks, 0, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), fused.view(torch.int16))
+
+
+def test_strided_variant_bad_arguments(gpu):
+    x = torch.zeros(1024 * 64, dtype=torch.bfloat16, device="cuda")
+    out = torch.empty_like(x)
+    for flags in (eq.RS_UNQUANTIZED | eq.AG_UNQUANTIZED, eq.SEMI_LOOP | eq.RS_UNQUANTIZED, eq.RING_ORDER,
+                  eq.RING_ORDER | eq.SEMI_LOOP, 16, 1 << 31):
+        with pytest.raises(eq.EquarxError) as e:
+            eq.equarx_reduce_variant_strided([x, x], 64, flags, out)
+        assert e.value.status == eq.STATUS_BAD_SHAPE
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_variant_strided([x, x], 48, 0, out)
+    assert e.value.status == eq.STATUS_BAD_BLOCK
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_variant_strided([x[:1024 * 32], x[:1024 * 32]], 64, 0, out[:1024 * 32])
+    assert e.value.status == eq.STATUS_BAD_SHAPE
+
+
 # ----------------------------------------------------------------------------- lengths beyond 32-bit indices
 
 def test_length_beyond_two_to_the_31(gpu, oracle):
