@@ -363,6 +363,30 @@ void do_hop_strided(const int8_t *cin, const float *sin, const void *x, int64_t 
 #undef CALL
 }
 
+// The single-launch chain and its flavours: chunks = 8 * W * R (see chain_strided_kernel), 4 * W workgroups per minishard.
+template <int R, int W>
+void launch_chain_strided_as(const PartialTable &tab, int P, unsigned grid, bool semi, bool rs, bool ag, uint16_t *out,
+                             LaunchCtx &ctx)
+{
+    if (semi && ag) ctx.launch(chain_strided_kernel<R, W, true, true, true>, grid, kThreads, tab, P, out);
+    else if (semi) ctx.launch(chain_strided_kernel<R, W, true, true, false>, grid, kThreads, tab, P, out);
+    else if (rs && ag) ctx.launch(chain_strided_kernel<R, W, false, true, true>, grid, kThreads, tab, P, out);
+    else if (rs) ctx.launch(chain_strided_kernel<R, W, false, true, false>, grid, kThreads, tab, P, out);
+    else ctx.launch(chain_strided_kernel<R, W, false, false, true>, grid, kThreads, tab, P, out);
+}
+
+void launch_chain_strided(const PartialTable &tab, int P, int64_t n, int32_t chunks, bool semi, bool rs, bool ag,
+                          uint16_t *out, LaunchCtx &ctx)
+{
+    const unsigned minishards = (unsigned)(n / ((int64_t)kChunk * chunks));
+    switch (chunks) {
+        case 32: launch_chain_strided_as<4, 1>(tab, P, minishards * 4, semi, rs, ag, out, ctx); break;
+        case 64: launch_chain_strided_as<8, 1>(tab, P, minishards * 4, semi, rs, ag, out, ctx); break;
+        case 128: launch_chain_strided_as<8, 2>(tab, P, minishards * 8, semi, rs, ag, out, ctx); break;
+        default: break;
+    }
+}
+
 void do_dequantize_strided(const int8_t *codes, const float *scales, int64_t n, int32_t chunks, void *out,
                            LaunchCtx &ctx)
 {
@@ -920,10 +944,7 @@ int equarx_reduce_fused_strided(const void *const *partials_bf16, int32_t P, int
     if (int st = fill_table(partials_bf16, P, n, mem, tab)) return st;
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
     if (int st = mem.check()) return st;
-#define CALL(RR) \
-    ctx.launch(chain_strided_kernel<RR>, strided_grid(n, chunks), kThreads, tab, P, static_cast<uint16_t *>(out_bf16))
-    EQUARX_DISPATCH_CHUNKS(chunks, CALL)
-#undef CALL
+    launch_chain_strided(tab, P, n, chunks, false, true, true, static_cast<uint16_t *>(out_bf16), ctx);
     return ctx.status();
 }
 
@@ -947,18 +968,7 @@ int equarx_reduce_variant_strided(const void *const *partials_bf16, int32_t P, i
     if (int st = fill_table(partials_bf16, P, n, mem, tab)) return st;
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
     if (int st = mem.check()) return st;
-    uint16_t *out = static_cast<uint16_t *>(out_bf16);
-    const unsigned grid = strided_grid(n, chunks);
-#define CALL(RR)                                                                                               \
-    do {                                                                                                       \
-        if (semi && ag) ctx.launch(variant_strided_kernel<RR, true, true, true>, grid, kThreads, tab, P, out); \
-        else if (semi) ctx.launch(variant_strided_kernel<RR, true, true, false>, grid, kThreads, tab, P, out); \
-        else if (rs && ag) ctx.launch(variant_strided_kernel<RR, false, true, true>, grid, kThreads, tab, P, out); \
-        else if (rs) ctx.launch(variant_strided_kernel<RR, false, true, false>, grid, kThreads, tab, P, out);  \
-        else ctx.launch(variant_strided_kernel<RR, false, false, true>, grid, kThreads, tab, P, out);          \
-    } while (0)
-    EQUARX_DISPATCH_CHUNKS(chunks, CALL)
-#undef CALL
+    launch_chain_strided(tab, P, n, chunks, semi, rs, ag, static_cast<uint16_t *>(out_bf16), ctx);
     return ctx.status();
 }
 

@@ -9,7 +9,10 @@
 // no cross-lane work at all (a lane keeps its own 8 positions), but a
 // reduction ACROSS the chunks of a minishard.
 //
-// Decomposition: a workgroup of 256 threads takes one slice of 256 positions of
+// Decomposition of the per-pass kernels (quantize, hop: codes go to memory, and
+// 8-byte code pieces want 16 lanes or more side by side to fill a 128-byte
+// line; the single-launch chain further down writes no codes and uses a
+// layout without LDS): a workgroup of 256 threads takes one slice of 256 positions of
 // one minishard.  Thread (g, l), g = 0..7, l = 0..31, owns positions 8l..8l+7
 // of the slice in chunks g, g+8, g+16, ...; it keeps the raw inputs of its
 // chunks/8 chunks in registers, so global memory is read once.  The 8 partial
@@ -23,8 +26,10 @@
 namespace equarx {
 
 constexpr int kChunk = 1024;                               // elements per chunk (8 x 128)
-// Measured at the 27B-shaped size: 32 lanes per slice is best overall (16: 5-35 % slower; 64: 3 % faster for 32
-// chunks, 30 % slower for 128).
+// Measured at the 27B-shaped size: 32 lanes per slice is best overall (16: within 2 % for 64 and 128 chunks, 8 %
+// slower for 32; 64: 3 % slower for 32, 30 % slower for 128).  Capping the waves per SIMD at 2 or 3, or dropping
+// the first of the two barriers (a kernel takes the maximum once), changes nothing beyond 2 %; the 8 x 8 in-wave
+// layout of the single-launch chain makes these kernels 5-8 % slower (64-byte code pieces).
 #ifndef EQUARX_STRIDED_SLICE_LANES
 #define EQUARX_STRIDED_SLICE_LANES 32
 #endif
@@ -193,122 +198,97 @@ __global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin
     }
 }
 
-// The whole full-loop chain (reduce-scatter and all-gather quantized) in one
-// launch, strided geometry: the running fp32 sums of a thread's chunks stay in
-// registers (8 * R floats), every hop costs one pass over a partial, one trip
-// through LDS and two barriers.  Same operations in the same order as the
-// hop-by-hop strided chain, hence the same bits.
-template <int R>
-__global__ __launch_bounds__(kThreads) void chain_strided_kernel(const PartialTable tab, int P,
-                                                                 uint16_t *out)
-{
-    __shared__ uint32_t red[kChunkGroups][kSlicePos];
-    constexpr int chunks = R * kChunkGroups;
-    const StridedSpot sp = strided_spot(chunks);
-
-    float t[R][8];
-    {
-        u32x4 xv[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            xv[r] = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x4 *>(tab.x[0] + sp.elem + (int64_t)r * kChunkGroups * kChunk));
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) widen_bf16x8(xv[r], t[r]);
-    }
-
-    for (int i = 1; i <= P; ++i) {
-        // what device i-1 sends (i < P), or what the all-gather carries (i == P): Q of the running sum
-        u32x4 xv[R];
-        if (i < P) {
-            const uint16_t *x = tab.x[i];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                xv[r] = __builtin_nontemporal_load(
-                    reinterpret_cast<const u32x4 *>(x + sp.elem + (int64_t)r * kChunkGroups * kChunk));
-            }
-        }
-        uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int r = 0; r < R; ++r) note_absmax(t[r], m);
-        across_chunks_max(m, red);
-        float scale[8], inv[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) block_quotients(__uint_as_float(m[j]), scale[j], inv[j]);
-        if (i < P) {
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                float xf[8];
-                widen_bf16x8(xv[r], xf);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float q = __builtin_rintf(t[r][j] * inv[j]);      // the code, as a float
-                    t[r][j] = __builtin_fmaf(q, scale[j], xf[j]);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                float d[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) d[j] = (__builtin_rintf(t[r][j] * inv[j]) + 0.0f) * scale[j];   // +0.0: see quantize_lane_f
-                u32x4 w;
-                w.x = narrow_bf16x2(d[0], d[1]);
-                w.y = narrow_bf16x2(d[2], d[3]);
-                w.z = narrow_bf16x2(d[4], d[5]);
-                w.w = narrow_bf16x2(d[6], d[7]);
-                __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(out + sp.elem + (int64_t)r * kChunkGroups * kChunk));
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------- flavours of the chain in the strided geometry
+// ---------------------------------------------------------------- the chain and its flavours in one launch
 //
-// The semi-loop reduce-scatter (Sec. 3.3) and the stage knob (Sec. 3.4), one
-// launch each, with the blocks of Sec. 3.2.  The running sums live in
-// registers as in chain_strided_kernel; a quantized send is one trip through
-// LDS for the scales of the lane's 8 positions.
+// The full-loop chain, the semi-loop reduce-scatter (Sec. 3.3) and the stage
+// knob (Sec. 3.4) with the blocks of Sec. 3.2, one launch each.  The running
+// fp32 sums of a thread's chunks stay in registers from the first partial to
+// the output; every quantized send needs the max-abs across the chunks of a
+// minishard and nothing else from other threads.
+//
+// Layout: lane = 8 * g + l inside a wave, so the 8 chunk groups of a position
+// sit in ONE wave, 8 lanes apart, and their maximum is three lane exchanges
+// per value -- no LDS, no barrier.  A wave covers 64 positions (a 128-byte
+// piece of each of 8 chunks per load) and, with W = 1, the chunks g, g+8, ...
+// of its group: R = chunks/8 rows of 8 running sums per thread.  For 128
+// chunks that would be 16 rows (128 sums, 64 load registers: one wave per
+// SIMD), so there W = 2 waves share a position piece, wave w taking the chunk
+// groups 8w .. 8w+7 (R = 8), and the two maxima meet through 256 bytes of LDS
+// and one barrier per send (the buffer alternates, so the barrier of the next
+// send also separates this send's reads from the writes of the one after).
+// Same operations in the same order as the hop-by-hop strided chain, hence
+// the same bits.
 
-template <int R>
-__device__ __forceinline__ void load_strided(const uint16_t *x, const StridedSpot &sp, u32x4 (&xv)[R])
+struct WaveSpot {
+    int64_t elem;       // first element of the lane in the first of its chunks
+    int64_t scale;      // index of the lane's first scale
+    int64_t row_step;   // elements between two consecutive chunks of the lane
+    bool first_group;   // the lane stores the scales of its 8 positions
+};
+
+// W waves per position piece; a 256-thread workgroup covers (4 / W) * 64 positions: 4 * W workgroups per minishard.
+template <int W>
+__device__ __forceinline__ WaveSpot wave_spot(int chunks)
+{
+    static_assert(W == 1 || W == 2, "waves per position piece");
+    constexpr int kPieces = (kThreads / 64) / W;                // position pieces per workgroup
+    constexpr int kPerChunk = kChunk / (kPieces * 64);          // workgroups per minishard
+    const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+    const int g = (wave % W) * 8 + lane / 8;                    // chunk group, 0 .. 8W-1
+    const int64_t ms = blockIdx.x / kPerChunk;
+    const int pos = (blockIdx.x % kPerChunk) * (kPieces * 64) + (wave / W) * 64 + (lane % 8) * kLaneElems;
+    WaveSpot sp;
+    sp.elem = ms * ((int64_t)kChunk * chunks) + (int64_t)g * kChunk + pos;
+    sp.scale = ms * kChunk + pos;
+    sp.row_step = (int64_t)8 * W * kChunk;
+    sp.first_group = g == 0;
+    return sp;
+}
+
+constexpr int strided_wave_share(int chunks) { return chunks > 64 ? 2 : 1; }       // W for a minishard of `chunks`
+
+// Max over all chunk groups for each of the lane's 8 positions.  Every thread of the workgroup calls this; `red`
+// and `parity` matter for W = 2 only.
+template <int W>
+__device__ __forceinline__ void across_chunks_max_wave(uint32_t (&m)[8], uint32_t (*red)[kThreads / 64][64], int &parity)
 {
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        xv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(x + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+    for (int j = 0; j < 8; ++j) {
+        uint32_t v = m[j];
+        v = umax(v, dpp_read<0x128>(v));                                    // row_ror:8: lane ^ 8 within a row of 16
+        auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);      // lane ^ 16
+        v = umax(a[0], a[1]);
+        auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);      // lane ^ 32
+        m[j] = umax(b[0], b[1]);
+    }
+    if (W == 2) {
+        const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+        const int at = (lane % 8) * kLaneElems;
+        if (lane < 8) {
+            u32x4 *row = reinterpret_cast<u32x4 *>(&red[parity][wave][at]);
+            row[0] = u32x4{m[0], m[1], m[2], m[3]};
+            row[1] = u32x4{m[4], m[5], m[6], m[7]};
+        }
+        __syncthreads();
+        const u32x4 *other = reinterpret_cast<const u32x4 *>(&red[parity][wave ^ 1][at]);
+        const u32x4 a = other[0], b = other[1];
+        m[0] = umax(m[0], a.x); m[1] = umax(m[1], a.y); m[2] = umax(m[2], a.z); m[3] = umax(m[3], a.w);
+        m[4] = umax(m[4], b.x); m[5] = umax(m[5], b.y); m[6] = umax(m[6], b.z); m[7] = umax(m[7], b.w);
+        parity ^= 1;
     }
 }
 
-// scale and inverse scale of the lane's 8 blocks for the sums t.  Every thread of the workgroup calls this.
-template <int R>
-__device__ __forceinline__ void strided_quotients(const float (&t)[R][8], uint32_t (*red)[kSlicePos], float (&scale)[8],
-                                                  float (&inv)[8])
-{
-    uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int r = 0; r < R; ++r) note_absmax(t[r], m);
-    across_chunks_max(m, red);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) block_quotients(__uint_as_float(m[j]), scale[j], inv[j]);
-}
+struct ChunkMaxState {
+    uint32_t (*red)[kThreads / 64][64];
+    int parity;
+};
 
-// One quantized send: acc <- fma(code(t), scale, acc).  kPositiveZero: the code of a value that rounds to zero is
-// +0.0 as the integer code's conversion is (needed only where the sign of a zero sum can reach the output, i.e.
-// when the all-gather is not quantized).
-template <int R, bool kPositiveZero>
-__device__ __forceinline__ void strided_send(const float (&t)[R][8], float (&acc)[R][8], uint32_t (*red)[kSlicePos])
+template <int R>
+__device__ __forceinline__ void load_strided(const uint16_t *x, const WaveSpot &sp, u32x4 (&xv)[R])
 {
-    float scale[8], inv[8];
-    strided_quotients<R>(t, red, scale, inv);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            float q = __builtin_rintf(t[r][j] * inv[j]);
-            if (kPositiveZero) q += 0.0f;
-            acc[r][j] = __builtin_fmaf(q, scale[j], acc[r][j]);
-        }
+        xv[r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(x + sp.elem + r * sp.row_step));
     }
 }
 
@@ -319,30 +299,75 @@ __device__ __forceinline__ void widen_strided(const u32x4 (&xv)[R], float (&t)[R
     for (int r = 0; r < R; ++r) widen_bf16x8(xv[r], t[r]);
 }
 
-// t <- fma(code(t), scale, x): what the device holding x has after it received the quantized t.
-template <int R, bool kPositiveZero>
-__device__ __forceinline__ void strided_hop(float (&t)[R][8], const u32x4 (&xv)[R], uint32_t (*red)[kSlicePos])
+// scale and inverse scale of the lane's 8 blocks for the sums t.
+template <int R, int W>
+__device__ __forceinline__ void strided_quotients(const float (&t)[R][8], ChunkMaxState &st, float (&scale)[8],
+                                                  float (&inv)[8])
 {
-    float next[R][8];
-    widen_strided<R>(xv, next);
-    strided_send<R, kPositiveZero>(t, next, red);
+    uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int r = 0; r < R; ++r) note_absmax(t[r], m);
+    across_chunks_max_wave<W>(m, st.red, st.parity);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) block_quotients(__uint_as_float(m[j]), scale[j], inv[j]);
+}
+
+// The code of v as a float.  kPositiveZero: a value that rounds to zero from below gives +0.0, as the integer
+// code converted back would (needed only where the sign of a zero sum can reach the output, i.e. when the
+// all-gather is not quantized).
+template <bool kPositiveZero>
+__device__ __forceinline__ float code_of(float v, float inv)
+{
+    const float q = __builtin_rintf(v * inv);
+    return kPositiveZero ? q + 0.0f : q;
+}
+
+// One hop: t <- fma(code(t), scale, x), what the device holding x has after it received the quantized t.
+template <int R, int W, bool kPositiveZero>
+__device__ __forceinline__ void strided_hop(float (&t)[R][8], const u32x4 (&xv)[R], ChunkMaxState &st)
+{
+    float scale[8], inv[8];
+    strided_quotients<R, W>(t, st, scale, inv);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
+        float xf[8];
+        widen_bf16x8(xv[r], xf);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) t[r][j] = next[r][j];
+        for (int j = 0; j < 8; ++j) t[r][j] = __builtin_fmaf(code_of<kPositiveZero>(t[r][j], inv[j]), scale[j], xf[j]);
     }
 }
 
-// kSemi: the semi-loop with partials[0] as the owner (always a quantized reduce-scatter); otherwise the full loop in
-// array order with the reduce-scatter quantized (kRS) or added in plain fp32.  kAG: the finished sum is quantized
-// once more and dequantized; otherwise narrowed to bf16 directly.
-template <int R, bool kSemi, bool kRS, bool kAG>
-__global__ __launch_bounds__(kThreads) void variant_strided_kernel(const PartialTable tab, int P, uint16_t *out)
+// The send that ends a half chain of the semi-loop: acc <- fma(code(t), scale, acc).
+template <int R, int W, bool kPositiveZero>
+__device__ __forceinline__ void strided_send_into(const float (&t)[R][8], float (&acc)[R][8], ChunkMaxState &st)
+{
+    float scale[8], inv[8];
+    strided_quotients<R, W>(t, st, scale, inv);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[r][j] = __builtin_fmaf(code_of<kPositiveZero>(t[r][j], inv[j]), scale[j], acc[r][j]);
+    }
+}
+
+// chunks = 8 * W * R.  kSemi: the semi-loop with partials[0] as the owner (always a quantized reduce-scatter);
+// otherwise the full loop in array order with the reduce-scatter quantized (kRS) or added in plain fp32.  kAG: the
+// finished sum is quantized once more and dequantized; otherwise narrowed to bf16 directly.
+// Waves per SIMD the compiler may plan for.  The full loop with a quantized reduce-scatter runs 3-4 us faster (of
+// 63-75 at the 27B-shaped size) held to two waves than at the four its ~120 registers would allow: the loads of one
+// partial per wave already fill the memory queues, and more waves only lengthen them.  The semi-loop (two dependent
+// half chains) and the unquantized reduce-scatter measured the other way round and keep the default.
+constexpr int strided_chain_waves(bool semi, bool rs) { return (!semi && rs) ? 2 : 8; }
+
+template <int R, int W, bool kSemi, bool kRS, bool kAG>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, strided_chain_waves(kSemi, kRS))))
+void chain_strided_kernel(const PartialTable tab, int P, uint16_t *out)
 {
     static_assert(kRS || !kSemi, "the semi-loop is a quantized reduce-scatter");
-    __shared__ uint32_t red[kChunkGroups][kSlicePos];
-    constexpr int chunks = R * kChunkGroups;
-    const StridedSpot sp = strided_spot(chunks);
+    __shared__ uint32_t red[W > 1 ? 2 : 1][kThreads / 64][64];
+    ChunkMaxState st{red, 0};
+    constexpr int chunks = 8 * W * R;
+    const WaveSpot sp = wave_spot<W>(chunks);
 
     float sum[R][8];
     u32x4 xv[R];
@@ -356,24 +381,24 @@ __global__ __launch_bounds__(kThreads) void variant_strided_kernel(const Partial
             widen_strided<R>(xv, t);
             for (int i = h + 2; i <= P - 1; ++i) {
                 load_strided<R>(tab.x[i], sp, xv);
-                strided_hop<R, !kAG>(t, xv, red);
+                strided_hop<R, W, !kAG>(t, xv, st);
             }
-            strided_send<R, !kAG>(t, sum, red);
+            strided_send_into<R, W, !kAG>(t, sum, st);
         }
         if (h >= 1) {                               // h -> h-1 -> ... -> 1 -> owner
             load_strided<R>(tab.x[h], sp, xv);
             widen_strided<R>(xv, t);
             for (int i = h - 1; i >= 1; --i) {
                 load_strided<R>(tab.x[i], sp, xv);
-                strided_hop<R, !kAG>(t, xv, red);
+                strided_hop<R, W, !kAG>(t, xv, st);
             }
-            strided_send<R, !kAG>(t, sum, red);
+            strided_send_into<R, W, !kAG>(t, sum, st);
         }
     } else {
         for (int i = 1; i < P; ++i) {
             load_strided<R>(tab.x[i], sp, xv);
             if (kRS) {
-                strided_hop<R, !kAG>(sum, xv, red);
+                strided_hop<R, W, !kAG>(sum, xv, st);
             } else {
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
@@ -387,20 +412,18 @@ __global__ __launch_bounds__(kThreads) void variant_strided_kernel(const Partial
     }
 
     float scale[8], inv[8];
-    if (kAG) strided_quotients<R>(sum, red, scale, inv);
+    if (kAG) strided_quotients<R, W>(sum, st, scale, inv);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         float d[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            d[j] = kAG ? (__builtin_rintf(sum[r][j] * inv[j]) + 0.0f) * scale[j] : sum[r][j];
-        }
+        for (int j = 0; j < 8; ++j) d[j] = kAG ? code_of<true>(sum[r][j], inv[j]) * scale[j] : sum[r][j];
         u32x4 w;
         w.x = narrow_bf16x2(d[0], d[1]);
         w.y = narrow_bf16x2(d[2], d[3]);
         w.z = narrow_bf16x2(d[4], d[5]);
         w.w = narrow_bf16x2(d[6], d[7]);
-        __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(out + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(out + sp.elem + r * sp.row_step));
     }
 }
 
