@@ -296,6 +296,27 @@ def main() -> int:
                 "inputs": f"cold ({S} input sets in turn)",
                 "wire": "none" if name == "fused" else "warm (read by the launch after the one that wrote it)",
             }
+        if everything:
+            # the same launches replayed from HIP graphs (one captured call per input set, at most 8): what a caller
+            # with a fixed set of buffers saves in launch cost; the entry points enqueue kernels only, so they capture
+            for name in wanted:
+                if name == "fused":
+                    continue
+                graphs = []
+                for k in range(min(S, 8)):
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=stream):
+                        calls[name](k)
+                    graphs.append(g)
+                gms = timed_steps(lambda k: graphs[k % len(graphs)].replay())
+                infos[name]["graph_replay"] = {
+                    "ms_per_step": round(gms, 5),
+                    "frac_of_hbm_peak": frac(own_bytes[name], gms),
+                    "graphs": len(graphs),
+                    "same_bits": bool(torch.equal(out.view(torch.int16), results[name].view(torch.int16)))
+                    if (K - 1) % len(graphs) == (K - 1) % S else None,
+                }
+                del graphs
         if "hop" in infos:
             # spread of single steps: the same K steps once more, each between two events on the stream (the records
             # themselves cost a microsecond or two per step, so the median sits slightly above ms_per_step)
