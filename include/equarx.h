@@ -332,6 +332,13 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
  *            combinations) except EQUARX_RING_ORDER, which this geometry does
  *            not offer (EQUARX_BAD_SHAPE).  flags == 0 gives the bits of
  *            equarx_reduce_fused_strided.  out_bf16 may BE one of the partials.
+ *   equarx_reduce_variant_hops_strided: the same flavours hop by hop, one launch
+ *            per send as a ring imposes (the paper's own setting: ring
+ *            schedule, strided blocks): flags EQUARX_SEMI_LOOP and / or
+ *            EQUARX_AG_UNQUANTIZED (anything else EQUARX_BAD_SHAPE); launches,
+ *            wire buffers and workspace as equarx_reduce_variant_hops with
+ *            block = chunks (equarx_variant_workspace_bytes(flags, P, n,
+ *            chunks) bytes, 256-byte aligned); same bits as the single launch.
  */
 int equarx_quantize_strided(const void *x_bf16, int64_t n, int32_t chunks,
                             int8_t *codes, float *scales, void *stream);
@@ -346,6 +353,9 @@ int equarx_reduce_fused_strided(const void *const *partials_bf16, int32_t P, int
                                 void *out_bf16, void *stream);
 int equarx_reduce_variant_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
                                   uint32_t flags, void *out_bf16, void *stream);
+int equarx_reduce_variant_hops_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
+                                       uint32_t flags, void *out_bf16, void *workspace, size_t workspace_bytes,
+                                       void *stream);
 
 /* Bytes of workspace equarx_reduce_quantized needs (0 for invalid arguments). */
 size_t equarx_workspace_bytes(int32_t P, int64_t n, int32_t block);

@@ -50,6 +50,8 @@ SIGNATURES = {
     "equarx_reduce_quantized_strided": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp, _sz, _vp]),
     "equarx_reduce_fused_strided": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, _vp, _vp]),
     "equarx_reduce_variant_strided": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp]),
+    "equarx_reduce_variant_hops_strided": (ctypes.c_int, [ctypes.POINTER(_vp), _i32, _i64, _i32, ctypes.c_uint32, _vp, _vp,
+                                                          _sz, _vp]),
     "equarx_workspace_bytes": (_sz, [_i32, _i64, _i32]),
     "equarx_num_blocks": (_i64, [_i64, _i32]),
     "equarx_wire_row_codes": (_i64, [_i64]),
@@ -400,6 +402,23 @@ def equarx_reduce_variant_strided(partials, chunks: int, flags: int, out_bf16) -
     table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
     _check(load().equarx_reduce_variant_strided(table, P, n, chunks, flags, _ptr(out_bf16), _stream()),
            "equarx_reduce_variant_strided")
+
+
+def equarx_reduce_variant_hops_strided(partials, chunks: int, flags: int, out_bf16, workspace) -> None:
+    """Full loop or semi-loop, all-gather quantized or not, hop by hop in the strided geometry."""
+    P = len(partials)
+    n = partials[0].numel() if P else 0
+    for p in partials:
+        _need(p, torch.bfloat16, n, "partial")
+        if p.numel() != n:
+            raise ValueError("partials differ in length")
+    _need(out_bf16, torch.bfloat16, n, "out_bf16")
+    if not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous CUDA tensor")
+    table = (_vp * max(P, 1))(*[p.data_ptr() for p in partials])
+    _check(load().equarx_reduce_variant_hops_strided(table, P, n, chunks, flags, _ptr(out_bf16), _ptr(workspace),
+                                                     workspace.numel() * workspace.element_size(), _stream()),
+           "equarx_reduce_variant_hops_strided")
 
 
 def equarx_calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:

@@ -363,6 +363,20 @@ void do_hop_strided(const int8_t *cin, const float *sin, const void *x, int64_t 
 #undef CALL
 }
 
+void do_owner_strided(const void *own, const StridedWires &wires, int received, int64_t n, int32_t chunks, bool ag,
+                      uint16_t *out, LaunchCtx &ctx)
+{
+#define CALL(RR)                                                                                                      \
+    do {                                                                                                              \
+        if (ag) ctx.launch(owner_strided_kernel<RR, true>, strided_grid(n, chunks), kThreads,                         \
+                           static_cast<const uint16_t *>(own), wires, received, out);                                 \
+        else ctx.launch(owner_strided_kernel<RR, false>, strided_grid(n, chunks), kThreads,                           \
+                        static_cast<const uint16_t *>(own), wires, received, out);                                    \
+    } while (0)
+    EQUARX_DISPATCH_CHUNKS(chunks, CALL)
+#undef CALL
+}
+
 // The single-launch chain and its flavours: chunks = 8 * W * R (see chain_strided_kernel), 4 * W workgroups per minishard.
 template <int R, int W>
 void launch_chain_strided_as(const PartialTable &tab, int P, unsigned grid, bool semi, bool rs, bool ag, uint16_t *out,
@@ -969,6 +983,80 @@ int equarx_reduce_variant_strided(const void *const *partials_bf16, int32_t P, i
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
     if (int st = mem.check()) return st;
     launch_chain_strided(tab, P, n, chunks, semi, rs, ag, static_cast<uint16_t *>(out_bf16), ctx);
+    return ctx.status();
+}
+
+int equarx_reduce_variant_hops_strided(const void *const *partials_bf16, int32_t P, int64_t n, int32_t chunks,
+                                       uint32_t flags, void *out_bf16, void *workspace, size_t workspace_bytes,
+                                       void *stream)
+{
+    LaunchCtx ctx(stream);
+    if (int st = check_strided(n, chunks)) return st;
+    if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
+    if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_AG_UNQUANTIZED)) return EQUARX_BAD_SHAPE;
+    const bool semi = flags & EQUARX_SEMI_LOOP, ag = !(flags & EQUARX_AG_UNQUANTIZED);
+    if (!partials_bf16) return EQUARX_NULL_POINTER;
+    if (n == 0) return EQUARX_OK;
+    if (!out_bf16 || !workspace) return EQUARX_NULL_POINTER;
+    if (misaligned(out_bf16, kAlign) || misaligned(workspace, kWorkspaceAlign)) return EQUARX_MISALIGNED;
+    // one scale per `chunks` elements: the contiguous variants' workspace with block = chunks
+    const size_t need = equarx_variant_workspace_bytes(flags, P, n, chunks);
+    if (workspace_bytes < need) return EQUARX_WORKSPACE_TOO_SMALL;
+    PartialTable tab;
+    Aliasing mem;
+    if (int st = fill_table(partials_bf16, P, n, mem, tab)) return st;
+    mem.writes(out_bf16, (size_t)n * 2, kInPlace);
+    mem.writes(workspace, need);
+    if (int st = mem.check()) return st;
+
+    const WireBuffers w = carve_workspace(workspace, n, n / chunks);
+    int8_t *const c[3] = {w.c[0], w.c[1], w.c[2]};
+    float *const s[3] = {w.s[0], w.s[1], w.s[2]};
+    uint16_t *out = static_cast<uint16_t *>(out_bf16);
+    StridedWires wires = {{nullptr, nullptr}, {nullptr, nullptr}};
+
+    if (!semi) {
+        // Q_B(x_0), hops 1 .. P-2, then the device holding x_(P-1) adds the last wire and feeds the all-gather
+        int received = 0;
+        if (P > 1) {
+            do_quantize_strided(tab.x[0], n, chunks, c[0], s[0], ctx);
+            for (int32_t i = 1; i + 1 < P; ++i) {
+                do_hop_strided(c[(i - 1) & 1], s[(i - 1) & 1], tab.x[i], n, chunks, c[i & 1], s[i & 1], ctx);
+            }
+            wires.codes[0] = c[(P - 2) & 1];
+            wires.scales[0] = s[(P - 2) & 1];
+            received = 1;
+        }
+        do_owner_strided(tab.x[P - 1], wires, received, n, chunks, ag, out, ctx);
+        return ctx.status();
+    }
+
+    // Semi-loop (Sec. 3.3): partial 0 owns the result; the chains h+1, ..., P-1 and h, h-1, ..., 1 each run hop by
+    // hop and end in a wire the owner receives, the shorter one first.
+    const int32_t h = P / 2, na = P - 1 - h, nbk = h;
+    int received = 0;
+    int last_a = -1;
+    if (na > 0) {
+        do_quantize_strided(tab.x[h + 1], n, chunks, c[0], s[0], ctx);
+        for (int32_t k = 1; k < na; ++k) {
+            do_hop_strided(c[(k - 1) & 1], s[(k - 1) & 1], tab.x[h + 1 + k], n, chunks, c[k & 1], s[k & 1], ctx);
+        }
+        last_a = (na - 1) & 1;
+        wires.codes[received] = c[last_a];
+        wires.scales[received] = s[last_a];
+        ++received;
+    }
+    if (nbk > 0) {
+        const int u[2] = {last_a == 0 ? 1 : 0, 2};      // two buffers that do not hold the first chain's wire
+        do_quantize_strided(tab.x[h], n, chunks, c[u[0]], s[u[0]], ctx);
+        for (int32_t k = 1; k < nbk; ++k) {
+            do_hop_strided(c[u[(k - 1) & 1]], s[u[(k - 1) & 1]], tab.x[h - k], n, chunks, c[u[k & 1]], s[u[k & 1]], ctx);
+        }
+        wires.codes[received] = c[u[(nbk - 1) & 1]];
+        wires.scales[received] = s[u[(nbk - 1) & 1]];
+        ++received;
+    }
+    do_owner_strided(tab.x[0], wires, received, n, chunks, ag, out, ctx);
     return ctx.status();
 }
 

@@ -198,6 +198,81 @@ __global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin
     }
 }
 
+// The last launch of a hop-by-hop flavour in the strided geometry: the device that ends up with the sum adds what
+// it received to its own bf16 shard -- one wire at the end of the full loop, one or two at the owner of the
+// semi-loop (Sec. 3.3: the shorter chain's wire first), none when it is alone -- each with one fused multiply-add
+// per element, and hands the sum to the all-gather: quantized once more and dequantized (kAG), or narrowed to
+// bf16 as it is (Sec. 3.4).  out may be `own`: a thread reads its elements before it writes them.
+struct StridedWires {
+    const int8_t *codes[2];
+    const float *scales[2];
+};
+
+template <int R, bool kAG>
+__global__ __launch_bounds__(kThreads) void owner_strided_kernel(const uint16_t *own, const StridedWires wires,
+                                                                 int received, uint16_t *out)
+{
+    __shared__ uint32_t red[kChunkGroups][kSlicePos];
+    constexpr int chunks = R * kChunkGroups;
+    const StridedSpot sp = strided_spot(chunks);
+
+    float acc[R][8];
+    {
+        u32x4 xv[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            xv[r] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(own + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) widen_bf16x8(xv[r], acc[r]);
+    }
+    for (int k = 0; k < received; ++k) {
+        const int8_t *codes = wires.codes[k];
+        const float *scales = wires.scales[k];
+        u32x2 cv[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            cv[r] = *reinterpret_cast<const u32x2 *>(codes + sp.elem + (int64_t)r * kChunkGroups * kChunk);
+        }
+        const u32x4 a = *reinterpret_cast<const u32x4 *>(scales + sp.scale);
+        const u32x4 b = *reinterpret_cast<const u32x4 *>(scales + sp.scale + 4);
+        const float s_in[8] = {__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(a.z), __uint_as_float(a.w),
+                               __uint_as_float(b.x), __uint_as_float(b.y), __uint_as_float(b.z), __uint_as_float(b.w)};
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float qf[8];
+            widen_i8x8(cv[r], qf);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[r][j] = __builtin_fmaf(qf[j], s_in[j], acc[r][j]);
+        }
+    }
+
+    float scale[8], inv[8];
+    if (kAG) {
+        uint32_t m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < R; ++r) note_absmax(acc[r], m);
+        across_chunks_max(m, red);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) block_quotients(__uint_as_float(m[j]), scale[j], inv[j]);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float d[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            d[j] = kAG ? (__builtin_rintf(acc[r][j] * inv[j]) + 0.0f) * scale[j] : acc[r][j];     // +0.0: the code as an integer
+        }
+        u32x4 w;
+        w.x = narrow_bf16x2(d[0], d[1]);
+        w.y = narrow_bf16x2(d[2], d[3]);
+        w.z = narrow_bf16x2(d[4], d[5]);
+        w.w = narrow_bf16x2(d[6], d[7]);
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x4 *>(out + sp.elem + (int64_t)r * kChunkGroups * kChunk));
+    }
+}
+
 // ---------------------------------------------------------------- the chain and its flavours in one launch
 //
 // The full-loop chain, the semi-loop reduce-scatter (Sec. 3.3) and the stage

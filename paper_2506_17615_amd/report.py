@@ -99,6 +99,10 @@ def main() -> int:
                              ("semi-loop RS+AG", eq.SEMI_LOOP), ("semi-loop RS only", eq.SEMI_LOOP | eq.AG_UNQUANTIZED)):
             rows.append((label + ", strided 8x128-chunk blocks",
                          lambda ps, flags=flags: eq.equarx_reduce_variant_strided(ps, B, flags, out)))
+            if not flags & eq.RS_UNQUANTIZED:
+                ws = work3 if flags & eq.SEMI_LOOP else work
+                rows.append((label + ", strided, hop by hop (P launches)",
+                             lambda ps, flags=flags, ws=ws: eq.equarx_reduce_variant_hops_strided(ps, B, flags, out, ws)))
 
     print(f"workload {w.name}: P={P}, n={n} ({w.rows} x {w.hidden}), block {B}, {w.dist}; MI355X, one GPU")
     print(f"{'flavour':58s} {'us':>8s} {'eff. input GB/s':>16s} {'MSE vs bf16 sum':>16s} {'rel-L2 vs exact':>16s}")

@@ -206,6 +206,20 @@ def test_validation_rejects_before_launch(lib):
     assert vs_(table(A, A, ODD, A), 4, ns, 64, B.SEMI_LOOP, OUT, None) == B.STATUS_MISALIGNED
     assert vs_(table(A, A, OUT + 16, A), 4, ns, 64, B.SEMI_LOOP, OUT, None) == B.STATUS_BAD_SHAPE
     assert vs_(None, 4, 0, 64, 0, None, None) == B.STATUS_NULL_POINTER and vs_(ok4, 4, 0, 64, B.SEMI_LOOP, None, None) == B.STATUS_OK
+    hs_ = lib.equarx_reduce_variant_hops_strided
+    need_s = lib.equarx_variant_workspace_bytes(B.SEMI_LOOP, 4, ns, 64)
+    assert hs_(ok4, 4, ns, 64, 0, None, WS, need_s, None) == B.STATUS_NULL_POINTER
+    assert hs_(ok4, 4, ns, 64, 0, OUT, None, need_s, None) == B.STATUS_NULL_POINTER
+    assert hs_(ok4, 4, ns, 96, 0, OUT, WS, need_s, None) == B.STATUS_BAD_BLOCK
+    assert hs_(ok4, 4, ns + 8, 64, 0, OUT, WS, need_s, None) == B.STATUS_BAD_SHAPE
+    assert hs_(ok4, 0, ns, 64, 0, OUT, WS, need_s, None) == B.STATUS_BAD_SHAPE
+    for bad_flags in (B.RING_ORDER, B.RS_UNQUANTIZED, 16):
+        assert hs_(ok4, 4, ns, 64, bad_flags, OUT, WS, need_s, None) == B.STATUS_BAD_SHAPE
+    assert hs_(ok4, 4, ns, 64, B.SEMI_LOOP, OUT, WS, need_s - 1, None) == B.STATUS_WORKSPACE_TOO_SMALL
+    assert hs_(ok4, 4, ns, 64, B.SEMI_LOOP, OUT, WS + 16, need_s, None) == B.STATUS_MISALIGNED
+    assert hs_(table(A, A, OUT + 16, A), 4, ns, 64, 0, OUT, WS, need_s, None) == B.STATUS_BAD_SHAPE
+    assert hs_(ok4, 4, ns, 64, 0, OUT, OUT, need_s, None) == B.STATUS_BAD_SHAPE                 # workspace = output
+    assert hs_(ok4, 4, 0, 64, B.SEMI_LOOP, None, None, 0, None) == B.STATUS_OK
     qb = lib.equarx_quantize_batch
     xs, cs, ss = table(A, A + 0x1000), table(A + 0x2000, A + 0x3000), table(A + 0x4000, A + 0x5000)
     assert qb(xs, cs, ss, 65, n, blk, None) == B.STATUS_BAD_SHAPE

@@ -1131,6 +1131,29 @@ def test_strided_variant_parity(gpu, oracle, name, chunks):
             assert (want == oracle.reduce_chain_strided(parts, chunks)).all()
 
 
+@pytest.mark.parametrize("name", ("full", "rs_only", "semi", "semi_rs_only"))
+@pytest.mark.parametrize("chunks", (32, 64, 128))
+def test_strided_variant_hop_by_hop_parity(gpu, oracle, name, chunks):
+    """The strided flavours in the ring-imposed schedule (one launch per send, wires in memory): the oracle's bits,
+    which are also the single launch's; every chain length of the semi-loop; output in place for some."""
+    flags = VARIANT_FLAGS[name]
+    ms = 1024 * chunks
+    for k, (P, count, kind) in enumerate([(1, 1, "normal"), (2, 2, "sparse"), (3, 1, "lognormal"), (4, 2, "tiny"),
+                                          (5, 3, "sparse"), (6, 1, "student"), (8, 2, "lognormal"), (9, 1, "huge")]):
+        n = count * ms
+        parts = [gpu.bf16_of(_values(kind, n, 9900 + 11 * p + P)) for p in range(P)]
+        want = _oracle_variant_strided(oracle, parts, chunks, flags)
+        dev = [gpu.dev_bf16(p) for p in parts]
+        out = dev[(P - 1) // 2] if k % 2 else torch.full((n,), 5.0, dtype=torch.bfloat16, device="cuda")
+        eq.equarx_reduce_variant_hops_strided(dev, chunks, flags, out, eq.alloc_variant_workspace(flags, P, n, chunks))
+        torch.cuda.synchronize()
+        got = gpu.host_u16(out)
+        assert (got == want).all(), (name, chunks, P, kind, int((got != want).sum()))
+        for i, d in enumerate(dev):
+            if d is not out:
+                assert (gpu.host_u16(d) == parts[i]).all(), (name, P, i)          # the other partials are untouched
+
+
 def test_strided_variant_full_size_sampled(gpu, oracle):
     """The Fig. 7 tensor ((4096, 4096), N(0,1), 8 devices, block 64 = 64 chunks) in the paper's own geometry, every
     flavour the figure compares: sampled minishards against the oracle, and the figure's error figures and their
@@ -1159,6 +1182,12 @@ def test_strided_variant_full_size_sampled(gpu, oracle):
             torch.cuda.synchronize()
             assert (gpu.host_u16(out)[idx] == _oracle_variant_strided(oracle, sub, chunks, flags)).all(), name
             mse[name] = float(((out.double() - base) ** 2).mean())
+            if name != "ag_only":       # without a quantized reduce-scatter there is no hop-by-hop form
+                hops = torch.full_like(out, 3.0)
+                eq.equarx_reduce_variant_hops_strided(dev, chunks, flags, hops,
+                                                      eq.alloc_variant_workspace(flags, w.P, w.n, chunks))
+                torch.cuda.synchronize()
+                assert torch.equal(hops.view(torch.int16), out.view(torch.int16)), name + " hop by hop"
     finally:
         oracle.set_threads(1)
     assert mse["ag_only"] < mse["semi"] < mse["full"] and mse["rs_only"] < mse["full"]
@@ -1179,6 +1208,14 @@ def test_strided_variant_bad_arguments(gpu):
         with pytest.raises(eq.EquarxError) as e:
             eq.equarx_reduce_variant_strided([x, x], 64, flags, out)
         assert e.value.status == eq.STATUS_BAD_SHAPE
+    ws = eq.alloc_variant_workspace(eq.SEMI_LOOP, 2, x.numel(), 64)
+    for flags in (eq.RS_UNQUANTIZED, eq.RING_ORDER, eq.RING_ORDER | eq.SEMI_LOOP, 16):
+        with pytest.raises(eq.EquarxError) as e:
+            eq.equarx_reduce_variant_hops_strided([x, x], 64, flags, out, ws)
+        assert e.value.status == eq.STATUS_BAD_SHAPE
+    with pytest.raises(eq.EquarxError) as e:
+        eq.equarx_reduce_variant_hops_strided([x, x], 64, eq.SEMI_LOOP, out, ws[:256])
+    assert e.value.status == eq.STATUS_WORKSPACE_TOO_SMALL
     with pytest.raises(eq.EquarxError) as e:
         eq.equarx_reduce_variant_strided([x, x], 48, 0, out)
     assert e.value.status == eq.STATUS_BAD_BLOCK
