@@ -6,8 +6,8 @@
 // over position j of every chunk, so a quantization block is `chunks` entries
 // that lie 1024 elements apart.  On the TPU this avoids any reduction inside a
 // vector register.  On a GPU it means the opposite of the contiguous layout:
-// no cross-lane work at all (a lane keeps its own 8 positions), but a
-// reduction ACROSS the chunks of a minishard.
+// no reduction over neighbouring elements (a lane keeps its own 8 positions),
+// but one ACROSS the chunks of a minishard.
 //
 // Decomposition of the per-pass kernels (quantize, hop: codes go to memory, and
 // 8-byte code pieces want 16 lanes or more side by side to fill a 128-byte
@@ -29,7 +29,8 @@ constexpr int kChunk = 1024;                               // elements per chunk
 // Measured at the 27B-shaped size: 32 lanes per slice is best overall (16: within 2 % for 64 and 128 chunks, 8 %
 // slower for 32; 64: 3 % slower for 32, 30 % slower for 128).  Capping the waves per SIMD at 2 or 3, or dropping
 // the first of the two barriers (a kernel takes the maximum once), changes nothing beyond 2 %; the 8 x 8 in-wave
-// layout of the single-launch chain makes these kernels 5-8 % slower (64-byte code pieces).
+// layout of the single-launch chain makes these kernels 5-8 % slower (64-byte code pieces); workgroups of 512 or 1024
+// threads with 1 or 2 KiB runs per chunk are no faster for 64 chunks and 4-100 % slower otherwise.
 #ifndef EQUARX_STRIDED_SLICE_LANES
 #define EQUARX_STRIDED_SLICE_LANES 32
 #endif
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(kThreads) void quantize_strided_kernel(const uint16
                                                                     int8_t *__restrict__ codes,
                                                                     float *__restrict__ scales)
 {
-    __shared__ uint32_t red[kChunkGroups][kSlicePos];
+    __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
     constexpr int chunks = R * kChunkGroups;
     const StridedSpot sp = strided_spot(chunks);
 
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin
                                                                const uint16_t *__restrict__ x, int8_t *cout,
                                                                float *sout)
 {
-    __shared__ uint32_t red[kChunkGroups][kSlicePos];
+    __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
     constexpr int chunks = R * kChunkGroups;
     const StridedSpot sp = strided_spot(chunks);
 
@@ -212,7 +213,7 @@ template <int R, bool kAG>
 __global__ __launch_bounds__(kThreads) void owner_strided_kernel(const uint16_t *own, const StridedWires wires,
                                                                  int received, uint16_t *out)
 {
-    __shared__ uint32_t red[kChunkGroups][kSlicePos];
+    __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
     constexpr int chunks = R * kChunkGroups;
     const StridedSpot sp = strided_spot(chunks);
 
@@ -439,7 +440,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, str
 void chain_strided_kernel(const PartialTable tab, int P, uint16_t *out)
 {
     static_assert(kRS || !kSemi, "the semi-loop is a quantized reduce-scatter");
-    __shared__ uint32_t red[W > 1 ? 2 : 1][kThreads / 64][64];
+    __shared__ __align__(16) uint32_t red[W > 1 ? 2 : 1][kThreads / 64][64];
     ChunkMaxState st{red, 0};
     constexpr int chunks = 8 * W * R;
     const WaveSpot sp = wave_spot<W>(chunks);
