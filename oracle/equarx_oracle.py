@@ -371,3 +371,25 @@ def reduce_semi_loop_strided(partials, chunks: int, quantize_ag: bool = True, li
     """The semi-loop chain (Sec. 3.3; partials[0] owns the result) in the strided block geometry (Sec. 3.2)."""
     moved = [to_block_major(_arr(p, np.uint16), chunks) for p in partials]
     return from_block_major(reduce_semi_loop(moved, chunks, quantize_ag, lib=lib), chunks)
+
+
+def reduce_ring_strided(partials, chunks: int, semi: bool = False, quantize_rs: bool = True, quantize_ag: bool = True,
+                        lib=None) -> np.ndarray:
+    """The ring layout (Sec. 3) with the blocks of Sec. 3.2: a device's shard is cut into minishards, so shards
+    are whole minishards here -- ceil(M/P) of the M minishards each, the last ones possibly short or empty --
+    and shard k ends on device k: reduced in the order ring_order(P, k), or with device k as the semi-loop's
+    owner and the devices k+1, k+2, ... around it."""
+    arrs = [_arr(p, np.uint16) for p in partials]
+    P, n = len(arrs), arrs[0].size
+    _check_strided(n, chunks)
+    out = np.empty(n, np.uint16)
+    for k, (lo, hi) in enumerate(shard_bounds(n, CHUNK * chunks, P)):
+        if hi <= lo:
+            continue
+        if not semi:
+            shard = [arrs[d][lo:hi] for d in ring_order(P, k)]
+            out[lo:hi] = reduce_stages_strided(shard, chunks, quantize_rs, quantize_ag, lib=lib)
+        else:
+            around = [arrs[(k + step) % P][lo:hi] for step in range(P)]
+            out[lo:hi] = reduce_semi_loop_strided(around, chunks, quantize_ag, lib=lib)
+    return out

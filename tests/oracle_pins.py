@@ -734,3 +734,48 @@ def pin_strided_variants(lib=None):
 
 
 ALL_PINS += [pin_strided_variants]
+
+
+def pin_ring_strided(lib=None):
+    """Ring layout with strided blocks (Sec. 3 with Sec. 3.2): shards are whole minishards and shard k ends on
+    device k.  Three devices, four minishards, so two per shard and an empty third shard; the minishard ranges and
+    every shard's device order are spelled out by hand and fed to the pinned strided flavours.  Identical
+    partials make the order irrelevant.  One position of one shard is also taken through the pinned CONTIGUOUS
+    chain on a plain strided gather in that shard's order, so neither the shard rule nor the order rests on a
+    strided function."""
+    chunks, P = 32, 3
+    ms = o.CHUNK * chunks
+    n = 4 * ms
+    parts = _chain_inputs(141, P, n, heavy=True)
+    shards = [(0, 2 * ms, (1, 2, 0), (0, 1, 2)), (2 * ms, 4 * ms, (2, 0, 1), (1, 2, 0))]     # lo, hi, full-loop order, owner first
+    plain = o.reduce_stages_strided(parts, chunks, lib=lib)
+    seen = set()
+    for rs, ag in ((True, True), (True, False), (False, True)):
+        got = o.reduce_ring_strided(parts, chunks, quantize_rs=rs, quantize_ag=ag, lib=lib)
+        seen.add(got.tobytes())
+        for lo, hi, chain, _ in shards:
+            want = o.reduce_stages_strided([parts[d][lo:hi] for d in chain], chunks, rs, ag)
+            assert (got[lo:hi] == want).all(), (rs, ag, lo)
+    for ag in (True, False):
+        got = o.reduce_ring_strided(parts, chunks, semi=True, quantize_ag=ag, lib=lib)
+        seen.add(got.tobytes())
+        for lo, hi, _, around in shards:
+            want = o.reduce_semi_loop_strided([parts[d][lo:hi] for d in around], chunks, ag)
+            assert (got[lo:hi] == want).all(), (ag, lo)
+    assert len(seen) == 5 and plain.tobytes() not in seen              # the rotation matters for every flavour
+    # one strided block of shard 1 (minishard 3, position 700) through the contiguous chain in the order 2, 0, 1
+    idx = 3 * ms + np.arange(chunks) * o.CHUNK + 700
+    got = o.reduce_ring_strided(parts, chunks, lib=lib)
+    assert (got[idx] == o.reduce_chain([parts[d][idx] for d in (2, 0, 1)], chunks)).all()
+    same = [parts[0]] * P
+    assert (o.reduce_ring_strided(same, chunks, lib=lib) == o.reduce_stages_strided(same, chunks)).all()
+    # a ring longer than the tensor has minishards: shards 0 and 1 hold one each, the rest are empty
+    P5 = 5
+    parts5 = _chain_inputs(142, P5, 2 * ms)
+    got = o.reduce_ring_strided(parts5, chunks, semi=True, lib=lib)
+    for k, around in enumerate(((0, 1, 2, 3, 4), (1, 2, 3, 4, 0))):
+        lo, hi = k * ms, (k + 1) * ms
+        assert (got[lo:hi] == o.reduce_semi_loop_strided([parts5[d][lo:hi] for d in around], chunks, True)).all(), k
+
+
+ALL_PINS += [pin_ring_strided]

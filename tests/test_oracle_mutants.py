@@ -121,12 +121,25 @@ PY_MUTANTS = {
                                       "from_block_major(reduce_stages(moved, chunks, True, quantize_ag, lib=lib), chunks)"),
     "strided_semi_contiguous_blocks": ("from_block_major(reduce_semi_loop(moved, chunks, quantize_ag, lib=lib), chunks)",
                                        "reduce_semi_loop([_arr(p, np.uint16) for p in partials], chunks, quantize_ag, lib=lib)"),
+    "ring_strided_shards_of_two_minishards": ("enumerate(shard_bounds(n, CHUNK * chunks, P))",
+                                              "enumerate(shard_bounds(n, 2 * CHUNK * chunks, P))"),
+    "ring_strided_no_rotation": ("shard = [arrs[d][lo:hi] for d in ring_order(P, k)]", "shard = [arrs[d][lo:hi] for d in range(P)]"),
+    "ring_strided_owner_off_by_one": ("around = [arrs[(k + step) % P][lo:hi] for step in range(P)]",
+                                      "around = [arrs[(k + 1 + step) % P][lo:hi] for step in range(P)]"),
+    "ring_strided_walks_backwards": ("around = [arrs[(k + step) % P][lo:hi] for step in range(P)]",
+                                     "around = [arrs[(k - step) % P][lo:hi] for step in range(P)]"),
+    "ring_strided_semi_flag_ignored": ("        if not semi:\n            shard =", "        if True:\n            shard ="),
+    "ring_strided_drops_rs_knob": ("reduce_stages_strided(shard, chunks, quantize_rs, quantize_ag, lib=lib)",
+                                   "reduce_stages_strided(shard, chunks, True, quantize_ag, lib=lib)"),
+    "ring_strided_contiguous_blocks": ("reduce_stages_strided(shard, chunks, quantize_rs, quantize_ag, lib=lib)",
+                                       "reduce_stages(shard, chunks, quantize_rs, quantize_ag, lib=lib)"),
     "shards_not_on_block_boundaries": ("per = (nb + P - 1) // P\n    return [(min(n, k * per * B), min(n, (k + 1) * per * B)) for k in range(P)]",
                                        "per = (n + P - 1) // P\n    return [(min(n, k * per), min(n, (k + 1) * per)) for k in range(P)]"),
 }
 
 
-FRONT_END = ("reduce_ring", "ring_order", "shard_bounds", "reduce_stages_strided", "reduce_semi_loop_strided")
+FRONT_END = ("reduce_ring", "ring_order", "shard_bounds", "reduce_stages_strided", "reduce_semi_loop_strided",
+             "reduce_ring_strided")
 
 
 def _mutated_front_end(tmp_path, old, new):
@@ -157,4 +170,5 @@ def test_unmutated_front_end_copy_passes(oracle, tmp_path, monkeypatch):
     mod = _mutated_front_end(tmp_path, "import ctypes\n", "import ctypes  \n")
     for attr in FRONT_END:
         monkeypatch.setattr(o, attr, getattr(mod, attr))
-    assert [p for p in ("pin_ring_order", "pin_ring_variants", "pin_strided_variants") if p in _failing_pins(None)] == []
+    assert [p for p in ("pin_ring_order", "pin_ring_variants", "pin_strided_variants", "pin_ring_strided")
+            if p in _failing_pins(None)] == []
