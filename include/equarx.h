@@ -329,9 +329,12 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
  *            geometry, one launch each: flags as for equarx_reduce_variant
  *            (EQUARX_SEMI_LOOP with partials[0] as the owner,
  *            EQUARX_RS_UNQUANTIZED, EQUARX_AG_UNQUANTIZED, same forbidden
- *            combinations) except EQUARX_RING_ORDER, which this geometry does
- *            not offer (EQUARX_BAD_SHAPE).  flags == 0 gives the bits of
- *            equarx_reduce_fused_strided.  out_bf16 may BE one of the partials.
+ *            combinations).  EQUARX_RING_ORDER cuts the tensor into P shards
+ *            of ceil(M/P) whole minishards (M = n / (1024 * chunks); a
+ *            device's shard is what the paper cuts into minishards), shard k
+ *            ending on device k as in equarx_reduce_variant.  flags == 0 gives
+ *            the bits of equarx_reduce_fused_strided.  out_bf16 may BE one of
+ *            the partials.
  *   equarx_reduce_variant_hops_strided: the same flavours hop by hop, one launch
  *            per send as a ring imposes (the paper's own setting: ring
  *            schedule, strided blocks): flags EQUARX_SEMI_LOOP and / or

@@ -379,24 +379,27 @@ void do_owner_strided(const void *own, const StridedWires &wires, int received, 
 
 // The single-launch chain and its flavours: chunks = 8 * W * R (see chain_strided_kernel), 4 * W workgroups per minishard.
 template <int R, int W>
-void launch_chain_strided_as(const PartialTable &tab, int P, unsigned grid, bool semi, bool rs, bool ag, uint16_t *out,
-                             LaunchCtx &ctx)
+void launch_chain_strided_as(const PartialTable &tab, int P, unsigned grid, int per_shard, bool semi, bool rs, bool ag,
+                             uint16_t *out, LaunchCtx &ctx)
 {
-    if (semi && ag) ctx.launch(chain_strided_kernel<R, W, true, true, true>, grid, kThreads, tab, P, out);
-    else if (semi) ctx.launch(chain_strided_kernel<R, W, true, true, false>, grid, kThreads, tab, P, out);
-    else if (rs && ag) ctx.launch(chain_strided_kernel<R, W, false, true, true>, grid, kThreads, tab, P, out);
-    else if (rs) ctx.launch(chain_strided_kernel<R, W, false, true, false>, grid, kThreads, tab, P, out);
-    else ctx.launch(chain_strided_kernel<R, W, false, false, true>, grid, kThreads, tab, P, out);
+    if (semi && ag) ctx.launch(chain_strided_kernel<R, W, true, true, true>, grid, kThreads, tab, P, per_shard, out);
+    else if (semi) ctx.launch(chain_strided_kernel<R, W, true, true, false>, grid, kThreads, tab, P, per_shard, out);
+    else if (rs && ag) ctx.launch(chain_strided_kernel<R, W, false, true, true>, grid, kThreads, tab, P, per_shard, out);
+    else if (rs) ctx.launch(chain_strided_kernel<R, W, false, true, false>, grid, kThreads, tab, P, per_shard, out);
+    else ctx.launch(chain_strided_kernel<R, W, false, false, true>, grid, kThreads, tab, P, per_shard, out);
 }
 
+// ring: shards of ceil(minishards / P) whole minishards, shard k in the order a ring gives it.
 void launch_chain_strided(const PartialTable &tab, int P, int64_t n, int32_t chunks, bool semi, bool rs, bool ag,
-                          uint16_t *out, LaunchCtx &ctx)
+                          bool ring, uint16_t *out, LaunchCtx &ctx)
 {
-    const unsigned minishards = (unsigned)(n / ((int64_t)kChunk * chunks));
+    const int64_t minishards = n / ((int64_t)kChunk * chunks);
+    const int per_shard = ring ? (int)((minishards + P - 1) / P) : 0;
+    const unsigned ms = (unsigned)minishards;
     switch (chunks) {
-        case 32: launch_chain_strided_as<4, 1>(tab, P, minishards * 4, semi, rs, ag, out, ctx); break;
-        case 64: launch_chain_strided_as<8, 1>(tab, P, minishards * 4, semi, rs, ag, out, ctx); break;
-        case 128: launch_chain_strided_as<8, 2>(tab, P, minishards * 8, semi, rs, ag, out, ctx); break;
+        case 32: launch_chain_strided_as<4, 1>(tab, P, ms * 4, per_shard, semi, rs, ag, out, ctx); break;
+        case 64: launch_chain_strided_as<8, 1>(tab, P, ms * 4, per_shard, semi, rs, ag, out, ctx); break;
+        case 128: launch_chain_strided_as<8, 2>(tab, P, ms * 8, per_shard, semi, rs, ag, out, ctx); break;
         default: break;
     }
 }
@@ -958,7 +961,7 @@ int equarx_reduce_fused_strided(const void *const *partials_bf16, int32_t P, int
     if (int st = fill_table(partials_bf16, P, n, mem, tab)) return st;
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
     if (int st = mem.check()) return st;
-    launch_chain_strided(tab, P, n, chunks, false, true, true, static_cast<uint16_t *>(out_bf16), ctx);
+    launch_chain_strided(tab, P, n, chunks, false, true, true, false, static_cast<uint16_t *>(out_bf16), ctx);
     return ctx.status();
 }
 
@@ -968,9 +971,10 @@ int equarx_reduce_variant_strided(const void *const *partials_bf16, int32_t P, i
     LaunchCtx ctx(stream);
     if (int st = check_strided(n, chunks)) return st;
     if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
-    if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_RS_UNQUANTIZED | EQUARX_AG_UNQUANTIZED)) return EQUARX_BAD_SHAPE;
+    if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_RS_UNQUANTIZED | EQUARX_AG_UNQUANTIZED | EQUARX_RING_ORDER))
+        return EQUARX_BAD_SHAPE;
     const bool semi = flags & EQUARX_SEMI_LOOP, rs = !(flags & EQUARX_RS_UNQUANTIZED);
-    const bool ag = !(flags & EQUARX_AG_UNQUANTIZED);
+    const bool ag = !(flags & EQUARX_AG_UNQUANTIZED), ring = flags & EQUARX_RING_ORDER;
     if (!rs && !ag) return EQUARX_BAD_SHAPE;        // nothing quantized
     if (semi && !rs) return EQUARX_BAD_SHAPE;       // the semi-loop is a reduce-scatter schedule
     if (!partials_bf16) return EQUARX_NULL_POINTER;
@@ -982,7 +986,7 @@ int equarx_reduce_variant_strided(const void *const *partials_bf16, int32_t P, i
     if (int st = fill_table(partials_bf16, P, n, mem, tab)) return st;
     mem.writes(out_bf16, (size_t)n * 2, kInPlace);
     if (int st = mem.check()) return st;
-    launch_chain_strided(tab, P, n, chunks, semi, rs, ag, static_cast<uint16_t *>(out_bf16), ctx);
+    launch_chain_strided(tab, P, n, chunks, semi, rs, ag, ring, static_cast<uint16_t *>(out_bf16), ctx);
     return ctx.status();
 }
 

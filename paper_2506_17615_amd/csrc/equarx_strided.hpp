@@ -296,6 +296,7 @@ __global__ __launch_bounds__(kThreads) void owner_strided_kernel(const uint16_t 
 // the same bits.
 
 struct WaveSpot {
+    int64_t minishard;  // which minishard the workgroup works on
     int64_t elem;       // first element of the lane in the first of its chunks
     int64_t scale;      // index of the lane's first scale
     int64_t row_step;   // elements between two consecutive chunks of the lane
@@ -314,6 +315,7 @@ __device__ __forceinline__ WaveSpot wave_spot(int chunks)
     const int64_t ms = blockIdx.x / kPerChunk;
     const int pos = (blockIdx.x % kPerChunk) * (kPieces * 64) + (wave / W) * 64 + (lane % 8) * kLaneElems;
     WaveSpot sp;
+    sp.minishard = ms;
     sp.elem = ms * ((int64_t)kChunk * chunks) + (int64_t)g * kChunk + pos;
     sp.scale = ms * kChunk + pos;
     sp.row_step = (int64_t)8 * W * kChunk;
@@ -426,53 +428,62 @@ __device__ __forceinline__ void strided_send_into(const float (&t)[R][8], float 
     }
 }
 
-// chunks = 8 * W * R.  kSemi: the semi-loop with partials[0] as the owner (always a quantized reduce-scatter);
-// otherwise the full loop in array order with the reduce-scatter quantized (kRS) or added in plain fp32.  kAG: the
-// finished sum is quantized once more and dequantized; otherwise narrowed to bf16 directly.
 // Waves per SIMD the compiler may plan for.  The full loop with a quantized reduce-scatter runs 3-4 us faster (of
 // 63-75 at the 27B-shaped size) held to two waves than at the four its ~120 registers would allow: the loads of one
 // partial per wave already fill the memory queues, and more waves only lengthen them.  The semi-loop (two dependent
 // half chains) and the unquantized reduce-scatter measured the other way round and keep the default.
 constexpr int strided_chain_waves(bool semi, bool rs) { return (!semi && rs) ? 2 : 8; }
 
+// chunks = 8 * W * R.  kSemi: the semi-loop with partials[0] as the owner (always a quantized reduce-scatter);
+// otherwise the full loop in array order with the reduce-scatter quantized (kRS) or added in plain fp32.  kAG: the
+// finished sum is quantized once more and dequantized; otherwise narrowed to bf16 directly.
+// Ring layout (Sec. 3): with per_shard > 0 the tensor is cut into shards of per_shard minishards and shard k ends
+// on device k: the full loop takes the partials in the order k+1, k+2, ..., k (mod P), the semi-loop has device k
+// as its owner and the devices k+1, k+2, ... around it.  per_shard == 0: array order everywhere.
 template <int R, int W, bool kSemi, bool kRS, bool kAG>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, strided_chain_waves(kSemi, kRS))))
-void chain_strided_kernel(const PartialTable tab, int P, uint16_t *out)
+void chain_strided_kernel(const PartialTable tab, int P, int per_shard, uint16_t *out)
 {
     static_assert(kRS || !kSemi, "the semi-loop is a quantized reduce-scatter");
     __shared__ __align__(16) uint32_t red[W > 1 ? 2 : 1][kThreads / 64][64];
     ChunkMaxState st{red, 0};
     constexpr int chunks = 8 * W * R;
     const WaveSpot sp = wave_spot<W>(chunks);
+    // position i of the chain -> partial; `first` <= P and i < P, so one conditional subtraction wraps
+    const int first = per_shard > 0 ? (int)(sp.minishard / per_shard) + (kSemi ? 0 : 1) : 0;
+    const auto part = [&](int i) {
+        const int j = first + i;
+        return tab.x[j >= P ? j - P : j];
+    };
 
     float sum[R][8];
     u32x4 xv[R];
-    load_strided<R>(tab.x[0], sp, xv);
+    load_strided<R>(part(0), sp, xv);
     widen_strided<R>(xv, sum);
     if (kSemi) {
         const int h = P / 2;
         float t[R][8];
         if (h + 1 <= P - 1) {                       // h+1 -> h+2 -> ... -> P-1 -> owner: the shorter chain arrives first
-            load_strided<R>(tab.x[h + 1], sp, xv);
+            load_strided<R>(part(h + 1), sp, xv);
             widen_strided<R>(xv, t);
             for (int i = h + 2; i <= P - 1; ++i) {
-                load_strided<R>(tab.x[i], sp, xv);
+                load_strided<R>(part(i), sp, xv);
                 strided_hop<R, W, !kAG>(t, xv, st);
             }
             strided_send_into<R, W, !kAG>(t, sum, st);
         }
         if (h >= 1) {                               // h -> h-1 -> ... -> 1 -> owner
-            load_strided<R>(tab.x[h], sp, xv);
+            load_strided<R>(part(h), sp, xv);
             widen_strided<R>(xv, t);
             for (int i = h - 1; i >= 1; --i) {
-                load_strided<R>(tab.x[i], sp, xv);
+                load_strided<R>(part(i), sp, xv);
                 strided_hop<R, W, !kAG>(t, xv, st);
             }
             strided_send_into<R, W, !kAG>(t, sum, st);
         }
     } else {
         for (int i = 1; i < P; ++i) {
-            load_strided<R>(tab.x[i], sp, xv);
+            load_strided<R>(part(i), sp, xv);
             if (kRS) {
                 strided_hop<R, W, !kAG>(sum, xv, st);
             } else {

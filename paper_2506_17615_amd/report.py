@@ -96,10 +96,12 @@ def main() -> int:
         rows.append(("full-loop RS+AG, strided 8x128-chunk blocks, one launch",
                      lambda ps: eq.equarx_reduce_fused_strided(ps, B, out)))
         for label, flags in (("full-loop RS only", eq.AG_UNQUANTIZED), ("full-loop AG only", eq.RS_UNQUANTIZED),
-                             ("semi-loop RS+AG", eq.SEMI_LOOP), ("semi-loop RS only", eq.SEMI_LOOP | eq.AG_UNQUANTIZED)):
+                             ("semi-loop RS+AG", eq.SEMI_LOOP), ("semi-loop RS only", eq.SEMI_LOOP | eq.AG_UNQUANTIZED),
+                             ("full-loop RS+AG, ring order", eq.RING_ORDER),
+                             ("semi-loop RS+AG, ring order", eq.SEMI_LOOP | eq.RING_ORDER)):
             rows.append((label + ", strided 8x128-chunk blocks",
                          lambda ps, flags=flags: eq.equarx_reduce_variant_strided(ps, B, flags, out)))
-            if not flags & eq.RS_UNQUANTIZED:
+            if not flags & (eq.RS_UNQUANTIZED | eq.RING_ORDER):
                 ws = work3 if flags & eq.SEMI_LOOP else work
                 rows.append((label + ", strided, hop by hop (P launches)",
                              lambda ps, flags=flags, ws=ws: eq.equarx_reduce_variant_hops_strided(ps, B, flags, out, ws)))

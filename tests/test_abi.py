@@ -201,7 +201,7 @@ def test_validation_rejects_before_launch(lib):
     vs_ = lib.equarx_reduce_variant_strided
     assert vs_(ok4, 4, ns, 64, 0, None, None) == B.STATUS_NULL_POINTER and vs_(ok4, 4, ns, 96, 0, OUT, None) == B.STATUS_BAD_BLOCK
     assert vs_(ok4, 4, ns + 8, 64, 0, OUT, None) == B.STATUS_BAD_SHAPE and vs_(ok4, 65, ns, 64, 0, OUT, None) == B.STATUS_BAD_SHAPE
-    for bad_flags in (B.RING_ORDER, B.RS_UNQUANTIZED | B.AG_UNQUANTIZED, B.SEMI_LOOP | B.RS_UNQUANTIZED, 16):
+    for bad_flags in (B.RS_UNQUANTIZED | B.AG_UNQUANTIZED, B.SEMI_LOOP | B.RS_UNQUANTIZED, B.RING_ORDER | B.RS_UNQUANTIZED | B.AG_UNQUANTIZED, 16):
         assert vs_(ok4, 4, ns, 64, bad_flags, OUT, None) == B.STATUS_BAD_SHAPE
     assert vs_(table(A, A, ODD, A), 4, ns, 64, B.SEMI_LOOP, OUT, None) == B.STATUS_MISALIGNED
     assert vs_(table(A, A, OUT + 16, A), 4, ns, 64, B.SEMI_LOOP, OUT, None) == B.STATUS_BAD_SHAPE

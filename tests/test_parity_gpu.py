@@ -1102,6 +1102,9 @@ STRIDED_VARIANTS = ("full", "rs_only", "ag_only", "semi", "semi_rs_only")
 
 def _oracle_variant_strided(oracle, parts, chunks, flags):
     ag = not (flags & eq.AG_UNQUANTIZED)
+    if flags & eq.RING_ORDER:
+        return oracle.reduce_ring_strided(parts, chunks, semi=bool(flags & eq.SEMI_LOOP),
+                                          quantize_rs=not (flags & eq.RS_UNQUANTIZED), quantize_ag=ag)
     if flags & eq.SEMI_LOOP:
         return oracle.reduce_semi_loop_strided(parts, chunks, ag)
     return oracle.reduce_stages_strided(parts, chunks, not (flags & eq.RS_UNQUANTIZED), ag)
@@ -1154,6 +1157,26 @@ def test_strided_variant_hop_by_hop_parity(gpu, oracle, name, chunks):
                 assert (gpu.host_u16(d) == parts[i]).all(), (name, P, i)          # the other partials are untouched
 
 
+@pytest.mark.parametrize("name", ("ring", "ring_rs_only", "ring_ag_only", "ring_semi", "ring_semi_rs_only"))
+@pytest.mark.parametrize("chunks", (32, 64, 128))
+def test_strided_variant_ring_order_parity(gpu, oracle, name, chunks):
+    """The ring layout in the strided geometry (shards of whole minishards, shard k ending on device k): rings
+    shorter than, as long as and longer than the tensor has minishards (short and empty shards)."""
+    flags = VARIANT_FLAGS[name]
+    ms = 1024 * chunks
+    for k, (P, count, kind) in enumerate([(1, 2, "normal"), (2, 3, "sparse"), (3, 4, "lognormal"), (4, 4, "student"),
+                                          (5, 2, "sparse"), (8, 11, "normal"), (9, 3, "tiny")]):
+        n = count * ms
+        parts = [gpu.bf16_of(_values(kind, n, 9950 + 11 * p + P)) for p in range(P)]
+        want = _oracle_variant_strided(oracle, parts, chunks, flags)
+        dev = [gpu.dev_bf16(p) for p in parts]
+        out = dev[P // 2] if k % 2 else torch.full((n,), 5.0, dtype=torch.bfloat16, device="cuda")
+        eq.equarx_reduce_variant_strided(dev, chunks, flags, out)
+        torch.cuda.synchronize()
+        got = gpu.host_u16(out)
+        assert (got == want).all(), (name, chunks, P, count, kind, int((got != want).sum()))
+
+
 def test_strided_variant_full_size_sampled(gpu, oracle):
     """The Fig. 7 tensor ((4096, 4096), N(0,1), 8 devices, block 64 = 64 chunks) in the paper's own geometry, every
     flavour the figure compares: sampled minishards against the oracle, and the figure's error figures and their
@@ -1188,6 +1211,13 @@ def test_strided_variant_full_size_sampled(gpu, oracle):
                                                       eq.alloc_variant_workspace(flags, w.P, w.n, chunks))
                 torch.cuda.synchronize()
                 assert torch.equal(hops.view(torch.int16), out.view(torch.int16)), name + " hop by hop"
+        # the ring layout at full size: 256 minishards, 32 per shard, every element against the oracle
+        for name in ("ring", "ring_semi"):
+            flags = VARIANT_FLAGS[name]
+            out.fill_(3.0)
+            eq.equarx_reduce_variant_strided(dev, chunks, flags, out)
+            torch.cuda.synchronize()
+            assert (gpu.host_u16(out) == _oracle_variant_strided(oracle, u16, chunks, flags)).all(), name
     finally:
         oracle.set_threads(1)
     assert mse["ag_only"] < mse["semi"] < mse["full"] and mse["rs_only"] < mse["full"]
@@ -1203,8 +1233,8 @@ def test_strided_variant_full_size_sampled(gpu, oracle):
 def test_strided_variant_bad_arguments(gpu):
     x = torch.zeros(1024 * 64, dtype=torch.bfloat16, device="cuda")
     out = torch.empty_like(x)
-    for flags in (eq.RS_UNQUANTIZED | eq.AG_UNQUANTIZED, eq.SEMI_LOOP | eq.RS_UNQUANTIZED, eq.RING_ORDER,
-                  eq.RING_ORDER | eq.SEMI_LOOP, 16, 1 << 31):
+    for flags in (eq.RS_UNQUANTIZED | eq.AG_UNQUANTIZED, eq.SEMI_LOOP | eq.RS_UNQUANTIZED,
+                  eq.RING_ORDER | eq.SEMI_LOOP | eq.RS_UNQUANTIZED, 16, 1 << 31):
         with pytest.raises(eq.EquarxError) as e:
             eq.equarx_reduce_variant_strided([x, x], 64, flags, out)
         assert e.value.status == eq.STATUS_BAD_SHAPE
