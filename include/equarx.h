@@ -337,11 +337,13 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
  *            the partials.
  *   equarx_reduce_variant_hops_strided: the same flavours hop by hop, one launch
  *            per send as a ring imposes (the paper's own setting: ring
- *            schedule, strided blocks): flags EQUARX_SEMI_LOOP and / or
- *            EQUARX_AG_UNQUANTIZED (anything else EQUARX_BAD_SHAPE); launches,
- *            wire buffers and workspace as equarx_reduce_variant_hops with
- *            block = chunks (equarx_variant_workspace_bytes(flags, P, n,
- *            chunks) bytes, 256-byte aligned); same bits as the single launch.
+ *            schedule, strided blocks): flags EQUARX_SEMI_LOOP,
+ *            EQUARX_AG_UNQUANTIZED, EQUARX_RING_ORDER (anything else
+ *            EQUARX_BAD_SHAPE); P launches (one when P == 1), each of them in
+ *            ring order one ring step on all P shards at once; workspace of
+ *            equarx_variant_workspace_bytes(flags without EQUARX_RING_ORDER,
+ *            P, n, chunks) bytes, 256-byte aligned (two wire buffers, three
+ *            for the semi-loop); same bits as the single launch.
  */
 int equarx_quantize_strided(const void *x_bf16, int64_t n, int32_t chunks,
                             int8_t *codes, float *scales, void *stream);

@@ -346,32 +346,52 @@ inline unsigned strided_grid(int64_t n, int32_t chunks)
         default: break;                      \
     }
 
-void do_quantize_strided(const void *x, int64_t n, int32_t chunks, int8_t *codes, float *scales, LaunchCtx &ctx)
+// One tensor as the source of a per-pass strided kernel.
+inline StridedSource one_tensor(const void *x)
 {
-#define CALL(RR) \
-    ctx.launch(quantize_strided_kernel<RR>, strided_grid(n, chunks), kThreads, static_cast<const uint16_t *>(x), codes, scales)
+    StridedSource src;
+    for (int i = 0; i < kMaxPartials; ++i) src.tab.x[i] = nullptr;
+    src.tab.x[0] = static_cast<const uint16_t *>(x);
+    src.P = 1;
+    src.per_shard = 0;
+    src.offset = 0;
+    return src;
+}
+
+// Partial `offset` of a chain (per_shard == 0), or in the ring layout the partial of device (k + offset) mod P for
+// every shard k at once (per_shard minishards per shard).
+inline StridedSource chain_source(const PartialTable &tab, int P, int per_shard, int offset)
+{
+    StridedSource src;
+    src.tab = tab;
+    src.P = P;
+    src.per_shard = per_shard;
+    src.offset = offset;
+    return src;
+}
+
+void do_quantize_strided(const StridedSource &src, int64_t n, int32_t chunks, int8_t *codes, float *scales, LaunchCtx &ctx)
+{
+#define CALL(RR) ctx.launch(quantize_strided_kernel<RR>, strided_grid(n, chunks), kThreads, src, codes, scales)
     EQUARX_DISPATCH_CHUNKS(chunks, CALL)
 #undef CALL
 }
 
-void do_hop_strided(const int8_t *cin, const float *sin, const void *x, int64_t n, int32_t chunks, int8_t *cout,
+void do_hop_strided(const int8_t *cin, const float *sin, const StridedSource &src, int64_t n, int32_t chunks, int8_t *cout,
                     float *sout, LaunchCtx &ctx)
 {
-#define CALL(RR) \
-    ctx.launch(hop_strided_kernel<RR>, strided_grid(n, chunks), kThreads, cin, sin, static_cast<const uint16_t *>(x), cout, sout)
+#define CALL(RR) ctx.launch(hop_strided_kernel<RR>, strided_grid(n, chunks), kThreads, cin, sin, src, cout, sout)
     EQUARX_DISPATCH_CHUNKS(chunks, CALL)
 #undef CALL
 }
 
-void do_owner_strided(const void *own, const StridedWires &wires, int received, int64_t n, int32_t chunks, bool ag,
+void do_owner_strided(const StridedSource &own, const StridedWires &wires, int received, int64_t n, int32_t chunks, bool ag,
                       uint16_t *out, LaunchCtx &ctx)
 {
-#define CALL(RR)                                                                                                      \
-    do {                                                                                                              \
-        if (ag) ctx.launch(owner_strided_kernel<RR, true>, strided_grid(n, chunks), kThreads,                         \
-                           static_cast<const uint16_t *>(own), wires, received, out);                                 \
-        else ctx.launch(owner_strided_kernel<RR, false>, strided_grid(n, chunks), kThreads,                           \
-                        static_cast<const uint16_t *>(own), wires, received, out);                                    \
+#define CALL(RR)                                                                                                           \
+    do {                                                                                                                   \
+        if (ag) ctx.launch(owner_strided_kernel<RR, true>, strided_grid(n, chunks), kThreads, own, wires, received, out);  \
+        else ctx.launch(owner_strided_kernel<RR, false>, strided_grid(n, chunks), kThreads, own, wires, received, out);    \
     } while (0)
     EQUARX_DISPATCH_CHUNKS(chunks, CALL)
 #undef CALL
@@ -883,7 +903,7 @@ int equarx_quantize_strided(const void *x_bf16, int64_t n, int32_t chunks, int8_
     mem.writes(codes, (size_t)n);
     mem.writes(scales, (size_t)(n / chunks) * sizeof(float));
     if (int st = mem.check()) return st;
-    do_quantize_strided(x_bf16, n, chunks, codes, scales, ctx);
+    do_quantize_strided(one_tensor(x_bf16), n, chunks, codes, scales, ctx);
     return ctx.status();
 }
 
@@ -915,7 +935,7 @@ int equarx_reduce_stage_strided(const int8_t *codes_in, const float *scales_in, 
         misaligned(codes_out, kAlign) || misaligned(scales_out, kAlign))
         return EQUARX_MISALIGNED;
     if (int st = check_hop_memory(codes_in, scales_in, local_bf16, n, n / chunks, codes_out, scales_out)) return st;
-    do_hop_strided(codes_in, scales_in, local_bf16, n, chunks, codes_out, scales_out, ctx);
+    do_hop_strided(codes_in, scales_in, one_tensor(local_bf16), n, chunks, codes_out, scales_out, ctx);
     return ctx.status();
 }
 
@@ -938,9 +958,9 @@ int equarx_reduce_quantized_strided(const void *const *partials_bf16, int32_t P,
     mem.writes(workspace, need);
     if (int st = mem.check()) return st;
     const WireBuffers w = carve_workspace(workspace, n, n / chunks);
-    do_quantize_strided(partials_bf16[0], n, chunks, w.c[0], w.s[0], ctx);
+    do_quantize_strided(one_tensor(partials_bf16[0]), n, chunks, w.c[0], w.s[0], ctx);
     for (int32_t i = 1; i < P; ++i) {
-        do_hop_strided(w.c[(i - 1) & 1], w.s[(i - 1) & 1], partials_bf16[i], n, chunks, w.c[i & 1], w.s[i & 1], ctx);
+        do_hop_strided(w.c[(i - 1) & 1], w.s[(i - 1) & 1], one_tensor(partials_bf16[i]), n, chunks, w.c[i & 1], w.s[i & 1], ctx);
     }
     do_dequantize_strided(w.c[(P - 1) & 1], w.s[(P - 1) & 1], n, chunks, out_bf16, ctx);
     return ctx.status();
@@ -997,14 +1017,14 @@ int equarx_reduce_variant_hops_strided(const void *const *partials_bf16, int32_t
     LaunchCtx ctx(stream);
     if (int st = check_strided(n, chunks)) return st;
     if (P < 1 || P > EQUARX_MAX_PARTIALS) return EQUARX_BAD_SHAPE;
-    if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_AG_UNQUANTIZED)) return EQUARX_BAD_SHAPE;
-    const bool semi = flags & EQUARX_SEMI_LOOP, ag = !(flags & EQUARX_AG_UNQUANTIZED);
+    if (flags & ~(uint32_t)(EQUARX_SEMI_LOOP | EQUARX_AG_UNQUANTIZED | EQUARX_RING_ORDER)) return EQUARX_BAD_SHAPE;
+    const bool semi = flags & EQUARX_SEMI_LOOP, ag = !(flags & EQUARX_AG_UNQUANTIZED), ring = flags & EQUARX_RING_ORDER;
     if (!partials_bf16) return EQUARX_NULL_POINTER;
     if (n == 0) return EQUARX_OK;
     if (!out_bf16 || !workspace) return EQUARX_NULL_POINTER;
     if (misaligned(out_bf16, kAlign) || misaligned(workspace, kWorkspaceAlign)) return EQUARX_MISALIGNED;
     // one scale per `chunks` elements: the contiguous variants' workspace with block = chunks
-    const size_t need = equarx_variant_workspace_bytes(flags, P, n, chunks);
+    const size_t need = equarx_variant_workspace_bytes(flags & ~(uint32_t)EQUARX_RING_ORDER, P, n, chunks);
     if (workspace_bytes < need) return EQUARX_WORKSPACE_TOO_SMALL;
     PartialTable tab;
     Aliasing mem;
@@ -1018,20 +1038,28 @@ int equarx_reduce_variant_hops_strided(const void *const *partials_bf16, int32_t
     float *const s[3] = {w.s[0], w.s[1], w.s[2]};
     uint16_t *out = static_cast<uint16_t *>(out_bf16);
     StridedWires wires = {{nullptr, nullptr}, {nullptr, nullptr}};
+    // Ring layout: shards of ceil(M / P) whole minishards; every launch is one ring step on all P shards at once,
+    // the workgroups of shard k reading the partial of device (k + offset) mod P.  Array order: offset = partial.
+    const int64_t minishards = n / ((int64_t)kChunk * chunks);
+    const int per_shard = ring ? (int)((minishards + P - 1) / P) : 0;
+    // position i of the full loop: a ring starts shard k's chain at device k+1 and ends it on device k
+    const auto at = [&](int i) { return chain_source(tab, P, per_shard, ring ? (i + 1) % P : i); };
+    // position i of the semi-loop counts from its owner: device k in a ring, partial 0 otherwise
+    const auto around = [&](int i) { return chain_source(tab, P, per_shard, i); };
 
     if (!semi) {
         // Q_B(x_0), hops 1 .. P-2, then the device holding x_(P-1) adds the last wire and feeds the all-gather
         int received = 0;
         if (P > 1) {
-            do_quantize_strided(tab.x[0], n, chunks, c[0], s[0], ctx);
+            do_quantize_strided(at(0), n, chunks, c[0], s[0], ctx);
             for (int32_t i = 1; i + 1 < P; ++i) {
-                do_hop_strided(c[(i - 1) & 1], s[(i - 1) & 1], tab.x[i], n, chunks, c[i & 1], s[i & 1], ctx);
+                do_hop_strided(c[(i - 1) & 1], s[(i - 1) & 1], at(i), n, chunks, c[i & 1], s[i & 1], ctx);
             }
             wires.codes[0] = c[(P - 2) & 1];
             wires.scales[0] = s[(P - 2) & 1];
             received = 1;
         }
-        do_owner_strided(tab.x[P - 1], wires, received, n, chunks, ag, out, ctx);
+        do_owner_strided(at(P - 1), wires, received, n, chunks, ag, out, ctx);
         return ctx.status();
     }
 
@@ -1041,9 +1069,9 @@ int equarx_reduce_variant_hops_strided(const void *const *partials_bf16, int32_t
     int received = 0;
     int last_a = -1;
     if (na > 0) {
-        do_quantize_strided(tab.x[h + 1], n, chunks, c[0], s[0], ctx);
+        do_quantize_strided(around(h + 1), n, chunks, c[0], s[0], ctx);
         for (int32_t k = 1; k < na; ++k) {
-            do_hop_strided(c[(k - 1) & 1], s[(k - 1) & 1], tab.x[h + 1 + k], n, chunks, c[k & 1], s[k & 1], ctx);
+            do_hop_strided(c[(k - 1) & 1], s[(k - 1) & 1], around(h + 1 + k), n, chunks, c[k & 1], s[k & 1], ctx);
         }
         last_a = (na - 1) & 1;
         wires.codes[received] = c[last_a];
@@ -1052,15 +1080,15 @@ int equarx_reduce_variant_hops_strided(const void *const *partials_bf16, int32_t
     }
     if (nbk > 0) {
         const int u[2] = {last_a == 0 ? 1 : 0, 2};      // two buffers that do not hold the first chain's wire
-        do_quantize_strided(tab.x[h], n, chunks, c[u[0]], s[u[0]], ctx);
+        do_quantize_strided(around(h), n, chunks, c[u[0]], s[u[0]], ctx);
         for (int32_t k = 1; k < nbk; ++k) {
-            do_hop_strided(c[u[(k - 1) & 1]], s[u[(k - 1) & 1]], tab.x[h - k], n, chunks, c[u[k & 1]], s[u[k & 1]], ctx);
+            do_hop_strided(c[u[(k - 1) & 1]], s[u[(k - 1) & 1]], around(h - k), n, chunks, c[u[k & 1]], s[u[k & 1]], ctx);
         }
         wires.codes[received] = c[u[(nbk - 1) & 1]];
         wires.scales[received] = s[u[(nbk - 1) & 1]];
         ++received;
     }
-    do_owner_strided(tab.x[0], wires, received, n, chunks, ag, out, ctx);
+    do_owner_strided(around(0), wires, received, n, chunks, ag, out, ctx);
     return ctx.status();
 }
 

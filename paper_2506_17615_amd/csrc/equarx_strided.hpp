@@ -41,6 +41,7 @@ constexpr int kSlicesPerChunk = kChunk / kSlicePos;        // 4 workgroups per m
 static_assert(kThreads == 256, "the strided kernels are laid out for 256-thread workgroups");
 
 struct StridedSpot {
+    int64_t minishard;  // which minishard the workgroup works on
     int64_t elem;       // first element of the lane in chunk `g` of its minishard
     int64_t scale;      // index of the lane's first scale
     int g;              // chunk group
@@ -53,9 +54,27 @@ __device__ __forceinline__ StridedSpot strided_spot(int chunks)
     sp.g = threadIdx.x / kSliceLanes;
     const int64_t ms = blockIdx.x / kSlicesPerChunk;
     const int pos = (blockIdx.x % kSlicesPerChunk) * kSlicePos + l * kLaneElems;
+    sp.minishard = ms;
     sp.elem = ms * ((int64_t)kChunk * chunks) + (int64_t)sp.g * kChunk + pos;
     sp.scale = ms * kChunk + pos;
     return sp;
+}
+
+// The bf16 tensor a per-pass kernel reads.  Array order (per_shard == 0): partial `offset` for every workgroup.
+// Ring layout (Sec. 3; per_shard > 0): the tensor is cut into shards of per_shard minishards, shard k ends on device
+// k, and a launch is one ring step on every shard at once -- the workgroups of shard k read the partial of device
+// (k + offset) mod P.  0 <= offset < P.
+struct StridedSource {
+    PartialTable tab;
+    int P;
+    int per_shard;
+    int offset;
+};
+
+__device__ __forceinline__ const uint16_t *strided_source(const StridedSource &src, int64_t minishard)
+{
+    const int j = (src.per_shard > 0 ? (int)(minishard / src.per_shard) : 0) + src.offset;     // < 2P
+    return src.tab.x[j >= src.P ? j - src.P : j];
 }
 
 // Max over the 8 chunk groups for each of the lane's 8 positions, through LDS.
@@ -97,13 +116,14 @@ __device__ __forceinline__ u32x2 scale_and_pack(const float (&t)[8], const float
 
 // R = chunks / 8 chunks per thread.
 template <int R>
-__global__ __launch_bounds__(kThreads) void quantize_strided_kernel(const uint16_t *__restrict__ x,
+__global__ __launch_bounds__(kThreads) void quantize_strided_kernel(const StridedSource src,
                                                                     int8_t *__restrict__ codes,
                                                                     float *__restrict__ scales)
 {
     __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
     constexpr int chunks = R * kChunkGroups;
     const StridedSpot sp = strided_spot(chunks);
+    const uint16_t *__restrict__ x = strided_source(src, sp.minishard);
 
     u32x4 xv[R];
 #pragma unroll
@@ -141,12 +161,12 @@ __global__ __launch_bounds__(kThreads) void quantize_strided_kernel(const uint16
 // workgroup holds all its inputs in registers before it stores anything.
 template <int R>
 __global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin, const float *sin,
-                                                               const uint16_t *__restrict__ x, int8_t *cout,
-                                                               float *sout)
+                                                               const StridedSource src, int8_t *cout, float *sout)
 {
     __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
     constexpr int chunks = R * kChunkGroups;
     const StridedSpot sp = strided_spot(chunks);
+    const uint16_t *__restrict__ x = strided_source(src, sp.minishard);
 
     u32x4 xv[R];
     u32x2 cv[R];
@@ -210,12 +230,13 @@ struct StridedWires {
 };
 
 template <int R, bool kAG>
-__global__ __launch_bounds__(kThreads) void owner_strided_kernel(const uint16_t *own, const StridedWires wires,
+__global__ __launch_bounds__(kThreads) void owner_strided_kernel(const StridedSource src, const StridedWires wires,
                                                                  int received, uint16_t *out)
 {
     __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
     constexpr int chunks = R * kChunkGroups;
     const StridedSpot sp = strided_spot(chunks);
+    const uint16_t *own = strided_source(src, sp.minishard);
 
     float acc[R][8];
     {

@@ -101,7 +101,7 @@ def main() -> int:
                              ("semi-loop RS+AG, ring order", eq.SEMI_LOOP | eq.RING_ORDER)):
             rows.append((label + ", strided 8x128-chunk blocks",
                          lambda ps, flags=flags: eq.equarx_reduce_variant_strided(ps, B, flags, out)))
-            if not flags & (eq.RS_UNQUANTIZED | eq.RING_ORDER):
+            if not flags & eq.RS_UNQUANTIZED:
                 ws = work3 if flags & eq.SEMI_LOOP else work
                 rows.append((label + ", strided, hop by hop (P launches)",
                              lambda ps, flags=flags, ws=ws: eq.equarx_reduce_variant_hops_strided(ps, B, flags, out, ws)))

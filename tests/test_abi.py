@@ -213,7 +213,7 @@ def test_validation_rejects_before_launch(lib):
     assert hs_(ok4, 4, ns, 96, 0, OUT, WS, need_s, None) == B.STATUS_BAD_BLOCK
     assert hs_(ok4, 4, ns + 8, 64, 0, OUT, WS, need_s, None) == B.STATUS_BAD_SHAPE
     assert hs_(ok4, 0, ns, 64, 0, OUT, WS, need_s, None) == B.STATUS_BAD_SHAPE
-    for bad_flags in (B.RING_ORDER, B.RS_UNQUANTIZED, 16):
+    for bad_flags in (B.RS_UNQUANTIZED, B.RING_ORDER | B.RS_UNQUANTIZED, 16):
         assert hs_(ok4, 4, ns, 64, bad_flags, OUT, WS, need_s, None) == B.STATUS_BAD_SHAPE
     assert hs_(ok4, 4, ns, 64, B.SEMI_LOOP, OUT, WS, need_s - 1, None) == B.STATUS_WORKSPACE_TOO_SMALL
     assert hs_(ok4, 4, ns, 64, B.SEMI_LOOP, OUT, WS + 16, need_s, None) == B.STATUS_MISALIGNED

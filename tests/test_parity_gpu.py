@@ -1134,7 +1134,8 @@ def test_strided_variant_parity(gpu, oracle, name, chunks):
             assert (want == oracle.reduce_chain_strided(parts, chunks)).all()
 
 
-@pytest.mark.parametrize("name", ("full", "rs_only", "semi", "semi_rs_only"))
+@pytest.mark.parametrize("name", ("full", "rs_only", "semi", "semi_rs_only", "ring", "ring_rs_only", "ring_semi",
+                                  "ring_semi_rs_only"))
 @pytest.mark.parametrize("chunks", (32, 64, 128))
 def test_strided_variant_hop_by_hop_parity(gpu, oracle, name, chunks):
     """The strided flavours in the ring-imposed schedule (one launch per send, wires in memory): the oracle's bits,
@@ -1148,7 +1149,8 @@ def test_strided_variant_hop_by_hop_parity(gpu, oracle, name, chunks):
         want = _oracle_variant_strided(oracle, parts, chunks, flags)
         dev = [gpu.dev_bf16(p) for p in parts]
         out = dev[(P - 1) // 2] if k % 2 else torch.full((n,), 5.0, dtype=torch.bfloat16, device="cuda")
-        eq.equarx_reduce_variant_hops_strided(dev, chunks, flags, out, eq.alloc_variant_workspace(flags, P, n, chunks))
+        ws = eq.alloc_variant_workspace(flags & ~eq.RING_ORDER, P, n, chunks)
+        eq.equarx_reduce_variant_hops_strided(dev, chunks, flags, out, ws)
         torch.cuda.synchronize()
         got = gpu.host_u16(out)
         assert (got == want).all(), (name, chunks, P, kind, int((got != want).sum()))
@@ -1218,6 +1220,11 @@ def test_strided_variant_full_size_sampled(gpu, oracle):
             eq.equarx_reduce_variant_strided(dev, chunks, flags, out)
             torch.cuda.synchronize()
             assert (gpu.host_u16(out) == _oracle_variant_strided(oracle, u16, chunks, flags)).all(), name
+            hops = torch.full_like(out, 3.0)
+            eq.equarx_reduce_variant_hops_strided(dev, chunks, flags, hops,
+                                                  eq.alloc_variant_workspace(flags & ~eq.RING_ORDER, w.P, w.n, chunks))
+            torch.cuda.synchronize()
+            assert torch.equal(hops.view(torch.int16), out.view(torch.int16)), name + " hop by hop"
     finally:
         oracle.set_threads(1)
     assert mse["ag_only"] < mse["semi"] < mse["full"] and mse["rs_only"] < mse["full"]
@@ -1239,7 +1246,7 @@ def test_strided_variant_bad_arguments(gpu):
             eq.equarx_reduce_variant_strided([x, x], 64, flags, out)
         assert e.value.status == eq.STATUS_BAD_SHAPE
     ws = eq.alloc_variant_workspace(eq.SEMI_LOOP, 2, x.numel(), 64)
-    for flags in (eq.RS_UNQUANTIZED, eq.RING_ORDER, eq.RING_ORDER | eq.SEMI_LOOP, 16):
+    for flags in (eq.RS_UNQUANTIZED, eq.RING_ORDER | eq.RS_UNQUANTIZED, 16):
         with pytest.raises(eq.EquarxError) as e:
             eq.equarx_reduce_variant_hops_strided([x, x], 64, flags, out, ws)
         assert e.value.status == eq.STATUS_BAD_SHAPE
