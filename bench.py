@@ -285,6 +285,8 @@ def main() -> int:
         results = {}
         wanted = list(calls) if everything else ([args.schedule] if args.only == "chain" else [])
         for name in wanted:
+            calls[name](0)      # not a step: the first call of a process loads the code object (tens of ms), also with --warmup 0
+            torch.cuda.synchronize()
             ms = timed_steps(calls[name])
             results[name] = out.clone()
             infos[name] = {
