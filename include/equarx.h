@@ -339,8 +339,10 @@ int equarx_reduce_flat(const void *local_bf16, const int8_t *const *codes, const
  *            per send as a ring imposes (the paper's own setting: ring
  *            schedule, strided blocks): flags EQUARX_SEMI_LOOP,
  *            EQUARX_AG_UNQUANTIZED, EQUARX_RING_ORDER (anything else
- *            EQUARX_BAD_SHAPE); P launches (one when P == 1), each of them in
- *            ring order one ring step on all P shards at once; workspace of
+ *            EQUARX_BAD_SHAPE); P launches for the full loop (one when
+ *            P == 1), P/2 + 1 for the semi-loop (its two chains advance in
+ *            the same launch), each of them in ring order one ring step on
+ *            all P shards at once; workspace of
  *            equarx_variant_workspace_bytes(flags without EQUARX_RING_ORDER,
  *            P, n, chunks) bytes, 256-byte aligned (two wire buffers, three
  *            for the semi-loop); same bits as the single launch.

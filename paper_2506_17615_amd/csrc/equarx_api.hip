@@ -1063,29 +1063,34 @@ int equarx_reduce_variant_hops_strided(const void *const *partials_bf16, int32_t
         return ctx.status();
     }
 
-    // Semi-loop (Sec. 3.3): partial 0 owns the result; the chains h+1, ..., P-1 and h, h-1, ..., 1 each run hop by
-    // hop and end in a wire the owner receives, the shorter one first.
-    const int32_t h = P / 2, na = P - 1 - h, nbk = h;
-    int received = 0;
-    int last_a = -1;
-    if (na > 0) {
-        do_quantize_strided(around(h + 1), n, chunks, c[0], s[0], ctx);
-        for (int32_t k = 1; k < na; ++k) {
-            do_hop_strided(c[(k - 1) & 1], s[(k - 1) & 1], around(h + 1 + k), n, chunks, c[k & 1], s[k & 1], ctx);
+    // Semi-loop (Sec. 3.3): the owner is position 0; the chain h+1, h+2, ..., P-1 (na sends) and the chain h, h-1,
+    // ..., 1 (nb >= na sends) each advance one device per launch, both in the same launch while both are under way
+    // (grid row = chain), each on a wire buffer of its own that its hops rewrite in place; the owner receives the
+    // shorter chain's wire first.
+    const int32_t h = P / 2, na = P - 1 - h, nb = h;
+    for (int32_t t = 0; t < nb; ++t) {
+        StridedDirections dirs;
+        dirs.d[0] = {h + 1 + t, t ? c[0] : nullptr, t ? s[0] : nullptr, c[0], s[0]};
+        dirs.d[1] = {h - t, t ? c[1] : nullptr, t ? s[1] : nullptr, c[1], s[1]};
+        if (t < na) {
+#define CALL(RR) ctx.launch2d(semi_step_strided_kernel<RR>, strided_grid(n, chunks), 2u, kThreads, tab, (int)P, per_shard, dirs)
+            EQUARX_DISPATCH_CHUNKS(chunks, CALL)
+#undef CALL
+        } else if (t == 0) {
+            do_quantize_strided(around(h), n, chunks, c[1], s[1], ctx);
+        } else {
+            do_hop_strided(c[1], s[1], around(h - t), n, chunks, c[1], s[1], ctx);
         }
-        last_a = (na - 1) & 1;
-        wires.codes[received] = c[last_a];
-        wires.scales[received] = s[last_a];
+    }
+    int received = 0;
+    if (na > 0) {
+        wires.codes[received] = c[0];
+        wires.scales[received] = s[0];
         ++received;
     }
-    if (nbk > 0) {
-        const int u[2] = {last_a == 0 ? 1 : 0, 2};      // two buffers that do not hold the first chain's wire
-        do_quantize_strided(around(h), n, chunks, c[u[0]], s[u[0]], ctx);
-        for (int32_t k = 1; k < nbk; ++k) {
-            do_hop_strided(c[u[(k - 1) & 1]], s[u[(k - 1) & 1]], around(h - k), n, chunks, c[u[k & 1]], s[u[k & 1]], ctx);
-        }
-        wires.codes[received] = c[u[(nbk - 1) & 1]];
-        wires.scales[received] = s[u[(nbk - 1) & 1]];
+    if (nb > 0) {
+        wires.codes[received] = c[1];
+        wires.scales[received] = s[1];
         ++received;
     }
     do_owner_strided(around(0), wires, received, n, chunks, ag, out, ctx);

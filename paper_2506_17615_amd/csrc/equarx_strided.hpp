@@ -116,15 +116,10 @@ __device__ __forceinline__ u32x2 scale_and_pack(const float (&t)[8], const float
 
 // R = chunks / 8 chunks per thread.
 template <int R>
-__global__ __launch_bounds__(kThreads) void quantize_strided_kernel(const StridedSource src,
-                                                                    int8_t *__restrict__ codes,
-                                                                    float *__restrict__ scales)
+__device__ __forceinline__ void quantize_strided_body(const uint16_t *__restrict__ x, int8_t *__restrict__ codes,
+                                                      float *__restrict__ scales, const StridedSpot &sp,
+                                                      uint32_t (*red)[kSlicePos])
 {
-    __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
-    constexpr int chunks = R * kChunkGroups;
-    const StridedSpot sp = strided_spot(chunks);
-    const uint16_t *__restrict__ x = strided_source(src, sp.minishard);
-
     u32x4 xv[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -157,17 +152,23 @@ __global__ __launch_bounds__(kThreads) void quantize_strided_kernel(const Stride
     }
 }
 
+template <int R>
+__global__ __launch_bounds__(kThreads) void quantize_strided_kernel(const StridedSource src,
+                                                                    int8_t *__restrict__ codes,
+                                                                    float *__restrict__ scales)
+{
+    __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
+    const StridedSpot sp = strided_spot(R * kChunkGroups);
+    quantize_strided_body<R>(strided_source(src, sp.minishard), codes, scales, sp, red);
+}
+
 // One hop in the strided geometry.  Output wire may be the input wire: a
 // workgroup holds all its inputs in registers before it stores anything.
 template <int R>
-__global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin, const float *sin,
-                                                               const StridedSource src, int8_t *cout, float *sout)
+__device__ __forceinline__ void hop_strided_body(const int8_t *cin, const float *sin, const uint16_t *__restrict__ x,
+                                                 int8_t *cout, float *sout, const StridedSpot &sp,
+                                                 uint32_t (*red)[kSlicePos])
 {
-    __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
-    constexpr int chunks = R * kChunkGroups;
-    const StridedSpot sp = strided_spot(chunks);
-    const uint16_t *__restrict__ x = strided_source(src, sp.minishard);
-
     u32x4 xv[R];
     u32x2 cv[R];
 #pragma unroll
@@ -216,6 +217,47 @@ __global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin
                                               __float_as_uint(scale[2]), __float_as_uint(scale[3])};
         *reinterpret_cast<u32x4 *>(s + 4) = u32x4{__float_as_uint(scale[4]), __float_as_uint(scale[5]),
                                                   __float_as_uint(scale[6]), __float_as_uint(scale[7])};
+    }
+}
+
+template <int R>
+__global__ __launch_bounds__(kThreads) void hop_strided_kernel(const int8_t *cin, const float *sin,
+                                                               const StridedSource src, int8_t *cout, float *sout)
+{
+    __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
+    const StridedSpot sp = strided_spot(R * kChunkGroups);
+    hop_strided_body<R>(cin, sin, strided_source(src, sp.minishard), cout, sout, sp, red);
+}
+
+// One iteration of the semi-loop reduce-scatter (Sec. 3.3) on both of its chains at once: grid row 0 advances the
+// chain that walks up from device h+1, row 1 the one that walks down from device h, each by one device -- the
+// first iteration quantizes the chain's first shard (no incoming wire: cin == nullptr), the later ones are hops on
+// the chain's own wire buffer in place.  The two rows share nothing.
+struct StridedDirection {
+    int offset;             // as StridedSource::offset
+    const int8_t *cin;      // nullptr: this is the chain's first device, it only quantizes its shard
+    const float *sin;
+    int8_t *cout;
+    float *sout;
+};
+
+struct StridedDirections {
+    StridedDirection d[2];
+};
+
+template <int R>
+__global__ __launch_bounds__(kThreads) void semi_step_strided_kernel(const PartialTable tab, int P, int per_shard,
+                                                                     const StridedDirections dirs)
+{
+    __shared__ __align__(16) uint32_t red[kChunkGroups][kSlicePos];
+    const StridedSpot sp = strided_spot(R * kChunkGroups);
+    const StridedDirection d = blockIdx.y == 0 ? dirs.d[0] : dirs.d[1];
+    const int j = (per_shard > 0 ? (int)(sp.minishard / per_shard) : 0) + d.offset;     // < 2P
+    const uint16_t *x = tab.x[j >= P ? j - P : j];
+    if (d.cin == nullptr) {             // uniform over the workgroup
+        quantize_strided_body<R>(x, d.cout, d.sout, sp, red);
+    } else {
+        hop_strided_body<R>(d.cin, d.sin, x, d.cout, d.sout, sp, red);
     }
 }
 

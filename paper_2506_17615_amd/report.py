@@ -103,7 +103,7 @@ def main() -> int:
                          lambda ps, flags=flags: eq.equarx_reduce_variant_strided(ps, B, flags, out)))
             if not flags & eq.RS_UNQUANTIZED:
                 ws = work3 if flags & eq.SEMI_LOOP else work
-                rows.append((label + ", strided, hop by hop (P launches)",
+                rows.append((label + ", strided, hop by hop",
                              lambda ps, flags=flags, ws=ws: eq.equarx_reduce_variant_hops_strided(ps, B, flags, out, ws)))
 
     print(f"workload {w.name}: P={P}, n={n} ({w.rows} x {w.hidden}), block {B}, {w.dist}; MI355X, one GPU")
